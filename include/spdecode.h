@@ -1,0 +1,181 @@
+/*
+ * spdecode: one decode step of parallel sampling on MI355X (gfx950).
+ *
+ * The paper's self-improvement loop draws many candidate completions from one
+ * long demonstration-augmented prompt (Alg. 1, "parallel sampling"; App.
+ * "Experiment settings": 64 samples per temperature, at most 1024 output
+ * tokens).  Inside the serving engine that step is, per generated token,
+ *
+ *   1. attention of every sample's single query row over the prompt's KV (shared
+ *      by all samples: the "prefix") and over the sample's own generated tokens
+ *      (the "suffix"), and
+ *   2. temperature sampling of the next token from the logits.
+ *
+ * This library provides exactly those two operations.  The attention is computed
+ * as a cascade: one pass treats all samples' queries of a KV head as a dense tile
+ * against the shared prefix (so the prefix is read once, not once per sample), a
+ * second pass streams each sample's private suffix, and the two partial softmax
+ * states are combined with the log-sum-exp rescaling of the online-softmax
+ * recurrence the paper prints for its attention tasks (App., attn tasks 0-2:
+ * running maximum m, running sum l, unnormalised accumulator, one final
+ * division).  The result equals softmax(q K^T * scale) V over the concatenated
+ * KV, which is the plain definition those tasks are verified against.
+ *
+ * Conventions for every entry point
+ *   - plain C ABI; no exceptions, no global mutable state.
+ *   - every data pointer is a DEVICE pointer owned by the caller unless marked
+ *     "host"; the library never allocates, frees or synchronises.  Scratch
+ *     memory comes from the caller's `workspace` (size from the matching
+ *     *_workspace_size call; 256-byte aligned).
+ *   - work is enqueued on `stream` (a hipStream_t, may be NULL for the default
+ *     stream) and the call returns without waiting.  Inputs are never written.
+ *   - the return value reports host-checkable errors only (spd_status).  Values
+ *     that only the device sees (lengths larger than the stated maxima, page ids
+ *     out of range, NaN logits, negative temperature) are the caller's
+ *     responsibility: results are then undefined.
+ *   - concurrent calls are safe if their workspaces and outputs are disjoint.
+ */
+#ifndef SPDECODE_H
+#define SPDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPD_API __attribute__((visibility("default")))
+
+typedef enum {
+    SPD_OK = 0,
+    SPD_EINVAL = 1,       /* NULL pointer, non-positive size, Hq % Hkv != 0, misaligned pointer */
+    SPD_EUNSUPPORTED = 2, /* dtype / head_dim / page_size outside the supported set */
+    SPD_EWORKSPACE = 3,   /* workspace missing, misaligned or too small */
+    SPD_ELAUNCH = 4       /* the HIP runtime refused a launch */
+} spd_status;
+
+typedef enum { SPD_F32 = 0, SPD_BF16 = 1 } spd_dtype;
+
+/* Stages of the attention call (for tests and per-kernel timing). 0 means all. */
+enum { SPD_STAGE_PREFIX = 1, SPD_STAGE_SUFFIX = 2, SPD_STAGE_MERGE = 4 };
+
+/*
+ * Problem description (host memory, read during the call only).
+ *
+ * N samples are grouped by prompt: prompt b owns the consecutive samples
+ * sample_indptr[b] .. sample_indptr[b+1]-1.  Query head h reads KV head
+ * h / (num_q_heads / num_kv_heads).
+ *
+ * Supported: dtype bf16 with head_dim 64 or 128 (MFMA path), dtype f32 with
+ * head_dim <= 256 (plain path); page_size 0 (contiguous KV) or 16.
+ */
+typedef struct spd_attn_desc {
+    int32_t dtype;                  /* spd_dtype of Q, K, V and the output */
+    int32_t num_q_heads;            /* Hq */
+    int32_t num_kv_heads;           /* Hkv, divides Hq */
+    int32_t head_dim;               /* D */
+    int32_t num_prompts;            /* B >= 1 */
+    int32_t num_samples;            /* N >= 1, total over all prompts */
+    int32_t max_samples_per_prompt; /* upper bound on sample_indptr[b+1]-sample_indptr[b]; 0 = N */
+    int32_t page_size;              /* 0 = contiguous KV, 16 = paged */
+    float sm_scale;                 /* score scale; <= 0 selects 1/sqrt(D) */
+    uint32_t stages;                /* 0 = whole call; else OR of SPD_STAGE_* */
+} spd_attn_desc;
+
+/* Bytes of workspace the attention call needs for these bounds (0 on invalid desc). */
+SPD_API size_t shared_prefix_decode_attn_workspace_size(const spd_attn_desc *desc,
+                                                int64_t max_prefix_len,
+                                                int64_t max_suffix_len);
+
+/*
+ * Attention of one decode step: out[n, h, :] = softmax(q[n, h] . K^T * scale) V
+ * over [prefix of n's prompt | suffix of n], K and V of KV head h / G.
+ * (Alg. 1 parallel sampling; App. attn tasks 0-2 for the softmax algebra.)
+ *
+ * Layouts (element type = desc->dtype, row-major, innermost dimension last):
+ *   q                 [N, Hq, D]
+ *   contiguous KV (page_size == 0)
+ *     k_prefix/v_prefix   [sum_b Lp_b, Hkv, D]; prompt b starts at token prefix_indptr[b]
+ *     k_suffix/v_suffix   [N, max_suffix_len, Hkv, D]; only the first suffix_lens[n]
+ *                         tokens of slot n are read
+ *   paged KV (page_size == 16)
+ *     k_prefix/v_prefix and k_suffix/v_suffix are page pools [num_pages, Hkv, 16, D]
+ *     (they may be the same pool).  Prompt b's pages are
+ *     prefix_page_indices[prefix_indptr[b] .. prefix_indptr[b+1]); sample n's are
+ *     suffix_page_indices[suffix_page_indptr[n] .. suffix_page_indptr[n+1]).  The last
+ *     page of a sequence may be partly filled; slots past the length are not read.
+ *   prefix_lens  int32 [B]     tokens in each prompt's prefix (0 allowed)
+ *   prefix_indptr int32 [B+1]  token offsets (contiguous) or page-list offsets (paged)
+ *   sample_indptr int32 [B+1]
+ *   suffix_lens  int32 [N]     tokens in each sample's suffix (0 allowed)
+ *   max_prefix_len / max_suffix_len  host-known upper bounds used to size the launch;
+ *                         max_suffix_len is also the slot stride of contiguous suffixes
+ *   out          [N, Hq, D], desc->dtype.  A sample with no KV at all gets zeros.
+ *   lse_out      float [N, Hq] natural-log log-sum-exp of the scaled scores, or NULL.
+ *                -inf for a sample with no KV.
+ *
+ * All pointers must be 16-byte aligned.  Returns spd_status.
+ */
+SPD_API int shared_prefix_decode_attn(const spd_attn_desc *desc,
+                              const void *q,
+                              const void *k_prefix, const void *v_prefix,
+                              const int32_t *prefix_lens,
+                              const int32_t *prefix_indptr,
+                              const int32_t *prefix_page_indices,
+                              const int32_t *sample_indptr,
+                              const void *k_suffix, const void *v_suffix,
+                              const int32_t *suffix_lens,
+                              const int32_t *suffix_page_indptr,
+                              const int32_t *suffix_page_indices,
+                              int64_t max_prefix_len, int64_t max_suffix_len,
+                              void *out, float *lse_out,
+                              void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+/* Bytes of workspace sample_tokens needs (0 on invalid sizes). */
+SPD_API size_t sample_tokens_workspace_size(int64_t rows, int64_t vocab);
+
+/*
+ * Next-token sampling at a temperature (App. "Experiment settings": the paper
+ * samples at temperatures 0.4, 0.7 and 1.0; it is silent on everything else, so
+ * the rule is fixed here).  Per row r, with x the row's logits:
+ *
+ *   p_i = exp((x_i - max x) / T_r);  S = sum p_i
+ *   nucleus: tau = the largest value t among the p_i with mass{p_i >= t} >= top_p_r * S
+ *            (tau = 0 when top_p_r >= 1); every token with p_i >= tau is kept, ties included
+ *   Z = mass of the kept tokens; walking the vocabulary in index order, the token
+ *   returned is the first kept i whose running kept mass exceeds uniforms[r] * Z.
+ *   T_r == 0 returns the lowest index attaining the maximum logit.
+ *
+ *   logits       fp32 [rows, vocab], row r at logits + r * row_stride (elements)
+ *   logits_dtype must be SPD_F32
+ *   temperature, top_p, uniforms   float [rows]; uniforms in [0, 1)
+ *   tokens_out   int32 [rows]
+ *
+ * Probabilities are evaluated in fp32 and accumulated in fp64 on the device.
+ * Returns spd_status.
+ */
+SPD_API int sample_tokens(const void *logits, int32_t logits_dtype,
+                  int64_t rows, int64_t vocab, int64_t row_stride,
+                  const float *temperature, const float *top_p, const float *uniforms,
+                  int32_t *tokens_out,
+                  void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* Short description of a status code (static storage). */
+SPD_API const char *spd_status_string(int status);
+
+/*
+ * Launch plan the attention call will use for these bounds (host arithmetic
+ * only).  Fills, when non-NULL: tokens per prefix split, number of prefix splits,
+ * tokens per suffix chunk, number of suffix chunks.  Returns spd_status.
+ */
+SPD_API int spd_attn_plan(const spd_attn_desc *desc, int64_t max_prefix_len, int64_t max_suffix_len,
+                  int32_t *prefix_split_tokens, int32_t *num_prefix_splits,
+                  int32_t *suffix_chunk_tokens, int32_t *num_suffix_chunks);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPDECODE_H */

@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of libspdecode.
+// Host-side launch wrappers take a filled AttnParams / SamplerParams; they do no
+// allocation and no synchronisation.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spd {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Unnormalised partial softmax state of one (sample, query head) over a token range:
+// running maximum m (in base-2 units of the scaled score), sum l of 2^(s - m) and the
+// accumulator sum 2^(s - m) v.  This is the deferred-division form of the paper's
+// online-softmax recurrence (App., attn task 2).  An empty range has l == 0.
+struct AttnParams {
+    int dtype, Hq, Hkv, D, G, B, N, max_spp, page_size;
+    float scale_log2;  // sm_scale * log2(e)
+    const void* q;
+    const void* k_prefix;
+    const void* v_prefix;
+    const int* prefix_lens;
+    const int* prefix_indptr;
+    const int* prefix_pages;
+    const int* sample_indptr;
+    const void* k_suffix;
+    const void* v_suffix;
+    const int* suffix_lens;
+    const int* suffix_page_indptr;
+    const int* suffix_pages;
+    long long max_suffix_len;
+    int prefix_split_tokens, num_prefix_splits;
+    int suffix_chunk_tokens, num_suffix_chunks;
+    float* part_acc;  // [slots][N*Hq][D]
+    float2* part_ml;  // [slots][N*Hq]  (m, l)
+    void* out;
+    float* lse;
+};
+
+struct SamplerParams {
+    const float* logits;
+    long long rows, vocab, stride;
+    const float* temperature;
+    const float* top_p;
+    const float* uniforms;
+    int* tokens;
+};
+
+// Prompt that owns sample n (sample_indptr is sorted, B >= 1).
+__device__ __forceinline__ int prompt_of_sample(const int* __restrict__ indptr, int B, int n)
+{
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (indptr[mid] <= n)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// Element offset of (token t, KV head j, channel 0) inside a KV tensor.
+//   contiguous: [token][Hkv][D], sequence starts at token `start`
+//   paged:      [page][Hkv][page_size][D], `pages` lists the sequence's pages
+__device__ __forceinline__ long long kv_row_offset(int t, int j, int Hkv, int D, int page_size,
+                                                   long long start, const int* __restrict__ pages)
+{
+    if (page_size == 0)
+        return ((start + t) * Hkv + j) * (long long)D;
+    const long long pg = pages[t / page_size];
+    return ((pg * Hkv + j) * page_size + (t % page_size)) * (long long)D;
+}
+
+hipError_t launch_attn_plain(const AttnParams& p, bool prefix, bool suffix, hipStream_t s);
+hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
+hipError_t launch_sampler(const SamplerParams& p, hipStream_t s);
+
+}  // namespace spd

@@ -1,0 +1,85 @@
+"""The C-ABI library loads and exports every symbol include/spdecode.h declares;
+host-side argument checks answer with status codes (no GPU needed, no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spdecode.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_02534_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"SPD_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)))
+
+
+def test_header_declares_the_two_entry_points():
+    names = declared_symbols()
+    assert "shared_prefix_decode_attn" in names and "sample_tokens" in names
+    assert len(names) >= 6
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    from paper_2502_02534_amd import binding as B
+    assert B.status_string(0) == "ok"
+    assert "workspace" in B.status_string(3)
+
+
+def test_plan_and_workspace_size_are_host_arithmetic(lib):
+    from paper_2502_02534_amd import binding as B
+    d = B.make_desc(dtype=B.SPD_BF16, num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1, num_samples=64)
+    pst, nps, sct, nsc = B.spd_attn_plan(d, 8192, 1024)
+    assert pst * nps >= 8192 and pst * (nps - 1) < 8192
+    assert sct * nsc >= 1024 and sct * (nsc - 1) < 1024
+    ws = B.shared_prefix_decode_attn_workspace_size(d, 8192, 1024)
+    assert ws >= (nps + nsc) * 64 * 32 * (128 + 2) * 4
+    assert B.sample_tokens_workspace_size(64, 128256) > 0
+    assert B.sample_tokens_workspace_size(0, 10) == 0
+
+
+def test_invalid_descriptions_are_rejected_on_the_host(lib):
+    from paper_2502_02534_amd import binding as B
+    bad = B.make_desc(dtype=B.SPD_BF16, num_q_heads=30, num_kv_heads=8, head_dim=128, num_prompts=1, num_samples=4)
+    assert B.shared_prefix_decode_attn_workspace_size(bad, 128, 128) == 0
+    with pytest.raises(B.SpdError) as e:
+        B.spd_attn_plan(bad, 128, 128)
+    assert e.value.status == 1
+    unsupported = B.make_desc(dtype=7, num_q_heads=8, num_kv_heads=8, head_dim=128, num_prompts=1, num_samples=4)
+    with pytest.raises(B.SpdError) as e:
+        B.spd_attn_plan(unsupported, 128, 128)
+    assert e.value.status == 2
+    paged = B.make_desc(dtype=B.SPD_BF16, num_q_heads=8, num_kv_heads=8, head_dim=128, num_prompts=1, num_samples=4, page_size=32)
+    with pytest.raises(B.SpdError):
+        B.spd_attn_plan(paged, 128, 128)
+
+
+def test_null_pointers_are_rejected_before_any_launch(lib):
+    from paper_2502_02534_amd import binding as B
+    d = B.make_desc(dtype=B.SPD_BF16, num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=1, num_samples=4)
+    z = ctypes.c_void_p(0)
+    rc = lib.shared_prefix_decode_attn(ctypes.byref(d), *([z] * 12), 128, 128, z, z, z, 0, z)
+    assert rc == 1
+    rc = lib.sample_tokens(z, 0, 4, 100, 100, z, z, z, z, z, 0, z)
+    assert rc == 1
+    one = ctypes.c_void_p(256)   # never dereferenced: the checks below fail first
+    assert lib.sample_tokens(one, 1, 4, 100, 100, one, one, one, one, one, 256, z) == 2     # bf16 logits
+    assert lib.sample_tokens(one, 0, 4, 100, 50, one, one, one, one, one, 256, z) == 1      # stride < vocab
+    assert lib.sample_tokens(one, 0, 4, 100, 100, one, one, one, one, z, 0, z) == 3         # no workspace
+    rc = lib.shared_prefix_decode_attn(ctypes.byref(d), *([one] * 12), 128, 128, one, z, one, 16, z)
+    assert rc == 3                                                                            # workspace too small

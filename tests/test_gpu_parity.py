@@ -1,0 +1,176 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 checker on the
+same seeded inputs.
+
+Tolerances
+  bf16 attention output : |gpu - ref| <= 2e-2 elementwise
+  fp32 attention output : |gpu - ref| <= 1e-5 |ref| + 1e-6 elementwise
+  log-sum-exp           : |gpu - ref| <= 1e-4 (fp32 arithmetic on values of order 10)
+  tokens                : identical, except rows whose uniform lies within 1e-6 of a
+                          boundary of the checker's CDF, or whose nucleus cut is within
+                          1e-6 (relative mass) of top_p * S; both kinds are counted.
+"""
+import numpy as np
+import pytest
+
+from paper_2502_02534_amd import workloads as W
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2502_02534_amd import binding
+    binding.load()          # raises if the HIP library is missing: no fallback
+    from paper_2502_02534_amd import device
+    return device
+
+
+def check_attention(dev, oracle, inp, rows=None, stages=0):
+    d = dev.upload_attn(inp)
+    d.out.fill_(float("nan"))
+    d.lse.fill_(float("nan"))
+    d.workspace.view(torch.float32)[: d.workspace.numel() // 4].fill_(float("nan"))
+    d.run(stages)
+    torch.cuda.synchronize()
+    got = d.out.float().cpu().numpy().astype(np.float64)
+    lse = d.lse.cpu().numpy().astype(np.float64)
+    D = inp.spec.head_dim
+    if rows is None:
+        ref, ref_lse = oracle.attention_inputs(inp)
+    else:
+        ref, ref_lse = oracle.attention_inputs(inp, rows=rows)
+        got = got.reshape(-1, D)[rows]
+        lse = lse.reshape(-1)[rows]
+    assert np.all(np.isfinite(got)), "non-finite output"
+    err = np.abs(got - ref)
+    if inp.spec.dtype == "f32":
+        assert np.all(err <= 1e-5 * np.abs(ref) + 1e-6), f"max err {err.max():.3e}"
+    else:
+        assert err.max() <= 2e-2, f"max err {err.max():.3e}"
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(ref_lse))
+    assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-4 + (0 if inp.spec.dtype == "f32" else 2e-3)), \
+        np.abs(lse[fin] - ref_lse[fin]).max()
+    return err.max()
+
+
+def check_tokens(dev, oracle, sin):
+    ds = dev.upload_sampler(sin)
+    ds.tokens.fill_(-7)
+    ds.run()
+    torch.cuda.synchronize()
+    tok = ds.tokens.cpu().numpy()
+    o = oracle.sample_tokens(sin.logits, sin.temperature, sin.top_p, sin.uniforms)
+    u = sin.uniforms.astype(np.float64)
+    near_cdf = np.minimum(np.abs(u - o["cdf_lo"]), np.abs(u - o["cdf_hi"])) < 1e-6
+    near_cut = o["cut_margin"] < 1e-6
+    mism = tok != o["token"]
+    hard = mism & ~near_cdf & ~near_cut
+    assert not hard.any(), (np.nonzero(hard)[0][:8], tok[hard][:8], o["token"][hard][:8])
+    assert np.all((tok >= 0) & (tok < sin.logits.shape[1]))
+    return int(near_cdf.sum()), int(near_cut.sum()), int(mism.sum())
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_attention_small_configs(dev, oracle, cfg):
+    print(f"attention cfg{cfg}", flush=True)
+    check_attention(dev, oracle, W.make_attn_inputs(cfg, poison_padding=True))
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_sampler_small_configs(dev, oracle, cfg):
+    print(f"sampler cfg{cfg}", flush=True)
+    check_tokens(dev, oracle, W.make_sampler_inputs(cfg))
+
+
+RAGGED = [
+    dict(dtype="f32", num_q_heads=6, num_kv_heads=3, head_dim=64, num_prompts=2, samples_per_prompt=5,
+         prefix_len=(1, 300), suffix_len=(0, 70)),
+    dict(dtype="f32", num_q_heads=4, num_kv_heads=1, head_dim=128, num_prompts=1, samples_per_prompt=3,
+         prefix_len=(0, 0), suffix_len=(0, 9)),
+    dict(dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=3, samples_per_prompt=7,
+         prefix_len=(1, 700), suffix_len=(0, 300)),
+    dict(dtype="bf16", num_q_heads=8, num_kv_heads=1, head_dim=128, num_prompts=1, samples_per_prompt=5,
+         prefix_len=(513, 513), suffix_len=(0, 0)),
+    dict(dtype="bf16", num_q_heads=16, num_kv_heads=2, head_dim=64, num_prompts=2, samples_per_prompt=9,
+         prefix_len=(65, 400), suffix_len=(1, 130)),
+    dict(dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=3, samples_per_prompt=6,
+         prefix_len=(1, 500), suffix_len=(0, 200), page_size=16),
+    dict(dtype="bf16", num_q_heads=4, num_kv_heads=4, head_dim=128, num_prompts=2, samples_per_prompt=33,
+         prefix_len=(100, 200), suffix_len=(0, 40), page_size=16),
+]
+
+
+@pytest.mark.parametrize("i", range(len(RAGGED)))
+def test_attention_ragged_and_degenerate(dev, oracle, i):
+    print(f"ragged attention case {i}: {RAGGED[i]}", flush=True)
+    inp = W.make_attn_inputs(0, spec=W.small_spec(**RAGGED[i]), seed=100 + i, poison_padding=True)
+    check_attention(dev, oracle, inp)
+
+
+def test_stage_masks_compose(dev, oracle):
+    """Running the stages one call at a time gives the same bits as one full call."""
+    from paper_2502_02534_amd import binding as B
+    inp = W.make_attn_inputs(2)
+    d = dev.upload_attn(inp)
+    d.run()
+    torch.cuda.synchronize()
+    full = d.out.clone()
+    d.out.zero_()
+    for st in (B.STAGE_PREFIX, B.STAGE_SUFFIX, B.STAGE_MERGE):
+        d.run(st)
+    torch.cuda.synchronize()
+    assert torch.equal(full.view(torch.int16), d.out.view(torch.int16))
+
+
+def _sampler_case(rows, vocab, sigma, T, top_p, seed, ties=False, stride_pad=0):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((rows, vocab + stride_pad)) * sigma).astype(np.float32)
+    if ties:
+        x = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x))     # bf16-valued logits: many exact ties
+    t = np.broadcast_to(np.asarray(T, np.float32), (rows,)).copy()
+    tp = np.broadcast_to(np.asarray(top_p, np.float32), (rows,)).copy()
+    return W.SamplerInputs(x[:, :vocab] if stride_pad == 0 else x, t, tp, rng.random(rows, dtype=np.float32))
+
+
+SAMPLER_CASES = [
+    dict(rows=7, vocab=1, sigma=3, T=0.7, top_p=0.9),
+    dict(rows=9, vocab=5, sigma=3, T=0.7, top_p=0.9),
+    dict(rows=33, vocab=4097, sigma=3, T=1.0, top_p=0.95),
+    dict(rows=16, vocab=32000, sigma=3, T=0.4, top_p=0.9),
+    dict(rows=16, vocab=50257, sigma=3, T=1.0, top_p=1.0),
+    dict(rows=16, vocab=50257, sigma=3, T=0.0, top_p=0.9),
+    dict(rows=16, vocab=32000, sigma=3, T=0.7, top_p=0.9, ties=True),
+    dict(rows=8, vocab=128256, sigma=3, T=1.2, top_p=0.95),
+    dict(rows=8, vocab=128256, sigma=3, T=0.2, top_p=0.5),
+    dict(rows=8, vocab=1000, sigma=0, T=1.0, top_p=0.9),           # all logits equal
+    dict(rows=8, vocab=1000, sigma=3, T=1.0, top_p=1e-6),          # nucleus = argmax only
+]
+
+
+@pytest.mark.parametrize("i", range(len(SAMPLER_CASES)))
+def test_sampler_cases(dev, oracle, i):
+    print(f"sampler case {i}: {SAMPLER_CASES[i]}", flush=True)
+    near_cdf, near_cut, mism = check_tokens(dev, oracle, _sampler_case(seed=500 + i, **SAMPLER_CASES[i]))
+    print(f"  exempt near-CDF rows {near_cdf}, nucleus-ambiguous rows {near_cut}, differing tokens {mism}")
+
+
+def test_sampler_mixed_per_row_parameters(dev, oracle):
+    rows = 64
+    rng = np.random.default_rng(77)
+    T = rng.choice([0.0, 0.2, 0.4, 0.7, 1.0, 1.2], size=rows)
+    tp = rng.choice([0.1, 0.5, 0.9, 0.95, 1.0], size=rows)
+    check_tokens(dev, oracle, _sampler_case(rows, 20011, 3, T, tp, 78))
+
+
+def test_sampler_is_deterministic(dev):
+    sin = W.make_sampler_inputs(2)
+    ds = dev.upload_sampler(sin)
+    ds.run()
+    torch.cuda.synchronize()
+    a = ds.tokens.clone()
+    ds.run()
+    torch.cuda.synchronize()
+    assert torch.equal(a, ds.tokens)
