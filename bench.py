@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark: shared-prefix attention (all layers) + token sampling.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+`shared_prefix_decode_attn` once per layer, then `sample_tokens` once.  Inputs
+are resident in HBM before the timed region.  To keep the caches from serving
+repeated reads, the step rotates over several copies of the inputs placed at
+distinct addresses (working set between reuses > 512 MB).
+
+Prints ONE JSON line (see the keys below).  `roofline` describes the kernel that
+takes the most time in a step; `kernels` lists every stage.  `cpu_baseline` is
+the fp64 checker timed on the host cores on the same workload (a reported
+baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2502_02534_amd import binding as B
+    from paper_2502_02534_amd import device, workloads
+
+    B.load()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sp = workloads.SPECS[args.config]
+    elt = 2 if sp.dtype == "bf16" else 4
+
+    # ---- inputs ---------------------------------------------------------------------------
+    layers_host = [workloads.make_attn_inputs(args.config, layer=l) for l in range(sp.layers)]
+    sin = workloads.make_sampler_inputs(args.config)
+    first = layers_host[0]
+    kvB = 2 * sp.num_kv_heads * sp.head_dim * elt                     # bytes per token, K and V, all heads
+    prefix_bytes = int(first.prefix_lens.astype(np.int64).sum()) * kvB
+    suffix_bytes = int(first.suffix_lens.astype(np.int64).sum()) * kvB
+    q_bytes = sp.num_samples * sp.num_q_heads * sp.head_dim * elt
+    sampler_bytes = sin.logits.shape[0] * sin.logits.shape[1] * 4 + 16 * sin.logits.shape[0]
+    step_bytes = sp.layers * (prefix_bytes + suffix_bytes + 2 * q_bytes) + sampler_bytes
+    prefix_flops = 4.0 * sp.group * sp.head_dim * sp.num_kv_heads * float(
+        sum(int(first.prefix_lens[b]) * int(first.sample_indptr[b + 1] - first.sample_indptr[b])
+            for b in range(sp.num_prompts)))
+    copies = args.copies or max(1, min(8, int(np.ceil(600e6 / max(step_bytes, 1)))))
+
+    sets = []
+    for c in range(copies):
+        lay = [device.upload_attn(h) for h in layers_host]
+        sets.append((lay, device.upload_sampler(sin)))
+    torch.cuda.synchronize()
+
+    def step(i: int) -> None:
+        lay, smp = sets[i % copies]
+        for d in lay:
+            d.run()
+        smp.run()
+
+    # ---- whole-step timing ----------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # ---- per-stage timing with events on the launching stream -------------------------------
+    def time_stage(fn, iters: int) -> float:
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3  # microseconds per call
+
+    def attn_stage(mask):
+        def fn(i):
+            lay, _ = sets[i % copies]
+            lay[i % len(lay)].run(mask)
+        return fn
+
+    it = args.kernel_iters
+    us = {
+        "prefix": time_stage(attn_stage(B.STAGE_PREFIX), it),
+        "suffix": time_stage(attn_stage(B.STAGE_SUFFIX), it),
+        "merge": time_stage(attn_stage(B.STAGE_MERGE), it),
+        "sampler": time_stage(lambda i: sets[i % copies][1].run(), it),
+    }
+    kernels = {
+        "prefix": {"us": us["prefix"], "bytes": prefix_bytes + q_bytes, "flops": prefix_flops,
+                   "GBps": (prefix_bytes + q_bytes) / us["prefix"] / 1e3,
+                   "TFLOPs": prefix_flops / us["prefix"] / 1e6, "calls_per_step": sp.layers},
+        "suffix": {"us": us["suffix"], "bytes": suffix_bytes + q_bytes,
+                   "GBps": (suffix_bytes + q_bytes) / us["suffix"] / 1e3, "calls_per_step": sp.layers},
+        "merge": {"us": us["merge"], "calls_per_step": sp.layers},
+        "sampler": {"us": us["sampler"], "bytes": sampler_bytes,
+                    "GBps": sampler_bytes / us["sampler"] / 1e3, "calls_per_step": 1},
+    }
+    for k in kernels.values():
+        k["frac_hbm_peak"] = k.get("GBps", 0.0) / HBM_PEAK_GBS
+    kernels["prefix"]["frac_mfma_peak"] = kernels["prefix"]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+    per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items()}
+    dom = max(per_step, key=per_step.get)
+    if dom == "prefix" and prefix_flops / MFMA_BF16_PEAK_TFLOPS / 1e12 > (prefix_bytes + q_bytes) / HBM_PEAK_GBS / 1e9:
+        roofline = {"kernel": "prefix", "bound": "mfma", "achieved": kernels["prefix"]["TFLOPs"],
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": kernels["prefix"]["frac_mfma_peak"], "traffic": None}
+    else:
+        if dom == "merge":
+            dom = "suffix"
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"], "traffic": None}
+
+    # ---- CPU baseline: the fp64 checker on the same workload ---------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        ncores = os.cpu_count() or 1
+        env_threads = int(os.environ.get("OMP_NUM_THREADS", ncores))
+        total_rows = sp.num_samples * sp.num_q_heads
+        # bounded sample: at most 256 attention rows of one layer and 32 sampler rows, scaled up
+        rows = np.arange(total_rows, dtype=np.int64)
+        if total_rows > 256:
+            rows = np.linspace(0, total_rows - 1, 256).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.attention_inputs(first, rows=rows)
+        t_attn = (time.perf_counter() - t0) * (total_rows / len(rows)) * sp.layers
+        srows = min(32, sin.logits.shape[0])
+        t0 = time.perf_counter()
+        oracle.sample_tokens(sin.logits[:srows], sin.temperature[:srows], sin.top_p[:srows], sin.uniforms[:srows])
+        t_samp = (time.perf_counter() - t0) * (sin.logits.shape[0] / srows)
+        cpu = {"value": 1.0 / (t_attn + t_samp), "unit": "steps/s", "cores": min(env_threads, ncores),
+               "kind": "oracle",
+               "sample": f"{len(rows)} of {total_rows} attention rows of one layer (x{sp.layers} layers) "
+                         f"and {srows} of {sin.logits.shape[0]} sampler rows, scaled linearly to one step"}
+
+    line = {
+        "metric": "decode_steps_per_sec", "value": 1e3 / ms_per_step, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": sp.dtype, "data": "synthetic",
+        "config": {"workload": sp.name, "config_id": args.config, "num_samples": sp.num_samples,
+                   "q_heads": sp.num_q_heads, "kv_heads": sp.num_kv_heads, "head_dim": sp.head_dim,
+                   "prefix_tokens": int(first.prefix_lens.sum()), "suffix_tokens": int(first.suffix_lens.sum()),
+                   "vocab": sp.vocab, "layers": sp.layers, "page_size": sp.page_size,
+                   "input_copies_rotated": copies},
+        "tokens_per_sec": sp.num_samples * 1e3 / ms_per_step,
+        "step_algorithmic_bytes": step_bytes,
+        "step_GBps": step_bytes / ms_per_step / 1e6,
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

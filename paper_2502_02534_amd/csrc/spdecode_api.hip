@@ -55,7 +55,17 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
         return SPD_EINVAL;
     pl->prefix_split_tokens = part_tokens(max_prefix, 256, 64, 64);
     pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
-    pl->suffix_chunk_tokens = part_tokens(max_suffix, 128, 64, 64);
+    {
+        // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..512 tokens
+        const long long pairs = (long long)d->num_samples * d->num_kv_heads;
+        const long long want_chunks = (4096 + pairs - 1) / pairs;
+        long long t = (max_suffix + want_chunks - 1) / want_chunks;
+        t = (t + 63) / 64 * 64;
+        if (t < 64) t = 64;
+        if (t > 512) t = 512;
+        if (max_suffix > t * 64) t = part_tokens(max_suffix, 64, 64, 64);
+        pl->suffix_chunk_tokens = (int)t;
+    }
     pl->num_suffix_chunks = (int)((max_suffix + pl->suffix_chunk_tokens - 1) / pl->suffix_chunk_tokens);
     const size_t rows = (size_t)d->num_samples * d->num_q_heads;
     const size_t slots = (size_t)pl->num_prefix_splits + pl->num_suffix_chunks;
@@ -177,9 +187,15 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
                                          : (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    e = spd::launch_attn_plain(p, stages & SPD_STAGE_PREFIX, stages & SPD_STAGE_SUFFIX, s);
+    const bool suffix_tiled = spd::suffix_mfma_supported(p);
+    e = spd::launch_attn_plain(p, stages & SPD_STAGE_PREFIX, (stages & SPD_STAGE_SUFFIX) && !suffix_tiled, s);
     if (e != hipSuccess)
         return SPD_ELAUNCH;
+    if ((stages & SPD_STAGE_SUFFIX) && suffix_tiled) {
+        e = spd::launch_attn_suffix_mfma(p, s);
+        if (e != hipSuccess)
+            return SPD_ELAUNCH;
+    }
     if (stages & SPD_STAGE_MERGE) {
         e = spd::launch_attn_merge(p, s);
         if (e != hipSuccess)
