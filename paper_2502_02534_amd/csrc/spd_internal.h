@@ -75,6 +75,9 @@ __device__ __forceinline__ long long kv_row_offset(int t, int j, int Hkv, int D,
 }
 
 hipError_t launch_attn_plain(const AttnParams& p, bool prefix, bool suffix, hipStream_t s);
+bool prefix_mfma_supported(const AttnParams& p);
+int prefix_mfma_block_rows(int rows);
+hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s);
 bool suffix_mfma_supported(const AttnParams& p);
 hipError_t launch_attn_suffix_mfma(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);

@@ -53,7 +53,22 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
         return rc;
     if (max_prefix < 0 || max_suffix < 0 || max_prefix > (1ll << 30) || max_suffix > (1ll << 30))
         return SPD_EINVAL;
-    pl->prefix_split_tokens = part_tokens(max_prefix, 256, 64, 64);
+    if (d->dtype == SPD_BF16 && d->head_dim == 128) {
+        // tiled path: one workgroup per (prompt, KV head, row tile, split); enough splits to
+        // occupy every CU once, in multiples of the 64-token tile
+        const int spp = d->max_samples_per_prompt > 0 ? d->max_samples_per_prompt : d->num_samples;
+        const int rows = spp * (d->num_q_heads / d->num_kv_heads);
+        const int block_rows = spd::prefix_mfma_block_rows(rows);
+        const long long base = (long long)d->num_prompts * d->num_kv_heads * ((rows + block_rows - 1) / block_rows);
+        long long want = (256 + base - 1) / base;
+        if (want > 64) want = 64;
+        long long t = (max_prefix + want - 1) / want;
+        t = (t + 63) / 64 * 64;
+        if (t < 64) t = 64;
+        pl->prefix_split_tokens = (int)t;
+    } else {
+        pl->prefix_split_tokens = part_tokens(max_prefix, 256, 64, 64);
+    }
     pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
     {
         // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..512 tokens
@@ -188,9 +203,16 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     const bool suffix_tiled = spd::suffix_mfma_supported(p);
-    e = spd::launch_attn_plain(p, stages & SPD_STAGE_PREFIX, (stages & SPD_STAGE_SUFFIX) && !suffix_tiled, s);
+    const bool prefix_tiled = spd::prefix_mfma_supported(p);
+    e = spd::launch_attn_plain(p, (stages & SPD_STAGE_PREFIX) && !prefix_tiled,
+                               (stages & SPD_STAGE_SUFFIX) && !suffix_tiled, s);
     if (e != hipSuccess)
         return SPD_ELAUNCH;
+    if ((stages & SPD_STAGE_PREFIX) && prefix_tiled) {
+        e = spd::launch_attn_prefix_mfma(p, s);
+        if (e != hipSuccess)
+            return SPD_ELAUNCH;
+    }
     if ((stages & SPD_STAGE_SUFFIX) && suffix_tiled) {
         e = spd::launch_attn_suffix_mfma(p, s);
         if (e != hipSuccess)
