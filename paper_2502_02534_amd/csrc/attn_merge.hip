@@ -20,61 +20,113 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// One block handles kRows rows; D threads per row (D <= 256, blockDim = kRows * Dpad).
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p, int rows_per_block, int dpad)
+constexpr int kMergeThreads = 256;
+constexpr int kMaxSlots = 128;   // prefix splits + suffix chunks (each at most 64)
+
+// One workgroup merges kMergeThreads / (D/4) rows; a thread owns 4 channels of one row.
+// Step 1 puts every valid partial's (m, l) in LDS, step 2 turns them into weights
+// 2^(m_i - m) (0 for empty partials) and the row's m and l, step 3 streams the accumulators
+// with eight independent 16-byte loads in flight per thread.
+__global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p, int tpr /* threads per row */)
 {
-    const int r_in = threadIdx.x / dpad;
-    const int d = threadIdx.x % dpad;
-    const long long row = (long long)blockIdx.x * rows_per_block + r_in;
+    __shared__ float2 ml[kMergeThreads / 8][kMaxSlots];   // at most 32 rows per block (D = 32)
+    __shared__ float wgt[kMergeThreads / 8][kMaxSlots];
+    __shared__ int slot_of[kMergeThreads / 8][kMaxSlots];
+    __shared__ int nvalid[kMergeThreads / 8];
+    __shared__ float row_m[kMergeThreads / 8], row_l[kMergeThreads / 8];
+
+    const int rows_per_block = kMergeThreads / tpr;
+    const int r_in = threadIdx.x / tpr;
+    const int c = threadIdx.x % tpr;  // channel group
     const long long total = (long long)p.N * p.Hq;
-    if (r_in >= rows_per_block || row >= total)
+    const long long row = (long long)blockIdx.x * rows_per_block + r_in;
+    const bool row_ok = row < total;
+
+    int np = 0, ns = 0;
+    if (row_ok) {
+        const int n = (int)(row / p.Hq);
+        const int b = prompt_of_sample(p.sample_indptr, p.B, n);
+        const int Lp = p.prefix_lens[b], Ls = p.suffix_lens[n];
+        np = p.prefix_split_tokens > 0 ? (Lp + p.prefix_split_tokens - 1) / p.prefix_split_tokens : 0;
+        ns = p.suffix_chunk_tokens > 0 ? (Ls + p.suffix_chunk_tokens - 1) / p.suffix_chunk_tokens : 0;
+    }
+    const int cnt = np + ns;
+    for (int i = c; i < cnt; i += tpr) {
+        const int slot = i < np ? i : p.num_prefix_splits + (i - np);
+        slot_of[r_in][i] = slot;
+        ml[r_in][i] = p.part_ml[(long long)slot * total + row];
+    }
+    __syncthreads();
+    if (c == 0) {
+        float m = -INFINITY;
+        for (int i = 0; i < cnt; ++i)
+            m = fmaxf(m, ml[r_in][i].x);
+        float l = 0.f;
+        for (int i = 0; i < cnt; ++i) {
+            const float2 v = ml[r_in][i];
+            const float w = v.y > 0.f ? __builtin_amdgcn_exp2f(v.x - m) : 0.f;
+            wgt[r_in][i] = w;
+            l = fmaf(v.y, w, l);
+        }
+        row_m[r_in] = m;
+        row_l[r_in] = l;
+        nvalid[r_in] = cnt;
+    }
+    __syncthreads();
+    if (!row_ok || 4 * c >= p.D)
         return;
-    const int n = (int)(row / p.Hq);
-    const int b = prompt_of_sample(p.sample_indptr, p.B, n);
-    const int Lp = p.prefix_lens[b], Ls = p.suffix_lens[n];
-    const int np = p.prefix_split_tokens > 0 ? (Lp + p.prefix_split_tokens - 1) / p.prefix_split_tokens : 0;
-    const int ns = p.suffix_chunk_tokens > 0 ? (Ls + p.suffix_chunk_tokens - 1) / p.suffix_chunk_tokens : 0;
-
-    float m = -INFINITY;
-    for (int i = 0; i < np; ++i)
-        m = fmaxf(m, p.part_ml[(long long)i * total + row].x);
-    for (int i = 0; i < ns; ++i)
-        m = fmaxf(m, p.part_ml[(long long)(p.num_prefix_splits + i) * total + row].x);
-
-    float l = 0.f, acc = 0.f;
-    const bool active = d < p.D;
-    for (int i = 0; i < np + ns; ++i) {
-        const long long slot = i < np ? i : p.num_prefix_splits + (i - np);
-        const float2 ml = p.part_ml[slot * total + row];
-        if (ml.y == 0.f)
-            continue;
-        const float w = __builtin_amdgcn_exp2f(ml.x - m);
-        l = fmaf(ml.y, w, l);
-        if (active)
-            acc = fmaf(p.part_acc[(slot * total + row) * p.D + d], w, acc);
+    const float l = row_l[r_in];
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* base = p.part_acc + row * p.D + 4 * c;
+    const long long slot_stride = total * p.D;
+    for (int i0 = 0; i0 < cnt; i0 += 8) {
+        float4 v[8];
+        float w[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u;
+            w[u] = i < cnt ? wgt[r_in][i] : 0.f;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (w[u] != 0.f)
+                v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_of[r_in][i] * slot_stride);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            acc.x = fmaf(v[u].x, w[u], acc.x);
+            acc.y = fmaf(v[u].y, w[u], acc.y);
+            acc.z = fmaf(v[u].z, w[u], acc.z);
+            acc.w = fmaf(v[u].w, w[u], acc.w);
+        }
     }
-    const float o = l > 0.f ? acc / l : 0.f;
-    if (active) {
-        if (p.dtype == 0)
-            ((float*)p.out)[row * p.D + d] = o;
-        else
-            ((uint16_t*)p.out)[row * p.D + d] = f32_to_bf16_rne(o);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    acc.x *= inv;
+    acc.y *= inv;
+    acc.z *= inv;
+    acc.w *= inv;
+    if (p.dtype == 0) {
+        *reinterpret_cast<float4*>((float*)p.out + row * p.D + 4 * c) = acc;
+    } else {
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16_rne(acc.x) | ((uint32_t)f32_to_bf16_rne(acc.y) << 16);
+        o.y = (uint32_t)f32_to_bf16_rne(acc.z) | ((uint32_t)f32_to_bf16_rne(acc.w) << 16);
+        *reinterpret_cast<uint2*>((uint16_t*)p.out + row * p.D + 4 * c) = o;
     }
-    if (p.lse && d == 0)
-        p.lse[row] = l > 0.f ? (m + __log2f(l)) * kLn2 : -INFINITY;
+    if (p.lse && c == 0)
+        p.lse[row] = l > 0.f ? (row_m[r_in] + __log2f(l)) * kLn2 : -INFINITY;
 }
 
 }  // namespace
 
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s)
 {
-    int dpad = 32;
-    while (dpad < p.D)
-        dpad <<= 1;
-    const int rows_per_block = 256 / dpad;
+    // threads per row: the power of two >= max(8, D/4); lanes past D/4 idle
+    int use = 8;
+    while (use * 4 < p.D)
+        use <<= 1;
+    const int rows_per_block = kMergeThreads / use;
     const long long total = (long long)p.N * p.Hq;
     const dim3 grid((unsigned)((total + rows_per_block - 1) / rows_per_block));
-    hipLaunchKernelGGL(attn_merge_kernel, grid, dim3(256), 0, s, p, rows_per_block, dpad);
+    hipLaunchKernelGGL(attn_merge_kernel, grid, dim3(kMergeThreads), 0, s, p, use);
     return hipGetLastError();
 }
 

@@ -230,7 +230,7 @@ size_t sample_tokens_workspace_size(int64_t rows, int64_t vocab)
 {
     if (rows <= 0 || vocab <= 0)
         return 0;
-    return 256;
+    return spd::sampler_workspace_bytes(rows, vocab);
 }
 
 int sample_tokens(const void* logits, int32_t logits_dtype, int64_t rows, int64_t vocab,
@@ -259,7 +259,7 @@ int sample_tokens(const void* logits, int32_t logits_dtype, int64_t rows, int64_
     p.top_p = top_p;
     p.uniforms = uniforms;
     p.tokens = tokens_out;
-    if (spd::launch_sampler(p, (hipStream_t)stream) != hipSuccess)
+    if (spd::launch_sampler(p, workspace, (hipStream_t)stream) != hipSuccess)
         return SPD_ELAUNCH;
     return SPD_OK;
 }
