@@ -2,9 +2,10 @@
 // a dense row tile against the shared prompt KV, so the prompt is read once per row
 // tile instead of once per sample.
 //
-// Workgroup = (prompt b, KV head j, tile of 64*WAVES query rows, split of the prefix).
-// A query row is (sample, head in group); each wavefront owns 64 rows (two 32-wide
-// column blocks of the transposed product).  K and V tiles of 64 tokens are loaded
+// Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix).
+// A query row is (sample, head in group); each wavefront owns 32 rows (one 32-wide
+// column block of the transposed product), two wavefronts share a SIMD so that one's
+// softmax overlaps the other's MFMAs.  K and V tiles of 64 tokens are loaded
 // cooperatively, 16 bytes per lane with 16 adjacent lanes per 256-byte row, and
 // double-buffered in LDS:
 //   K  row-major [token][channel] (padded rows), read as the A operand of
@@ -37,12 +38,15 @@ __device__ __forceinline__ uint32_t dword(const uint4& v, int k)
     return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Two floats to packed bf16 (round to nearest even): one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    const f32x2 v = {lo, hi};
+    const bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<const uint32_t*>(&r);
 }
 
 // Token (relative to the tile) of element e (0..7) of V fragment f (0..7).  Fragment
@@ -53,11 +57,12 @@ __device__ __forceinline__ int frag_token(int f, int e)
     return 16 * (f >> 1) + 4 * (f & 1) + (e < 4 ? e : e + 4);
 }
 
-template <int WAVES, bool PAGED>
+template <int WAVES, int NB, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams p)
 {
     constexpr int kThreads = WAVES * 64;
-    constexpr int kTasks = 256 / kThreads;  // load tasks per thread per tile
+    constexpr int kRowsPerWave = 32 * NB;
+    constexpr int kTasks = (256 + kThreads - 1) / kThreads;  // load tasks per thread per tile
     __shared__ uint4 ksm[2][kTileN][kKRowU4];
     __shared__ uint4 vsm[2][kD][kVRowU4];
 
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     const int b = blockIdx.z / p.Hkv, j = blockIdx.z % p.Hkv;
     const int s0 = p.sample_indptr[b];
     const int rows_b = (p.sample_indptr[b + 1] - s0) * p.G;
-    const int row0 = rowtile * 64 * WAVES;
+    const int row0 = rowtile * kRowsPerWave * WAVES;
     const int Lp = p.prefix_lens[b];
     const int t0 = split * p.prefix_split_tokens;
     const int t1 = min(Lp, t0 + p.prefix_split_tokens);
@@ -91,12 +96,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     };
 
     // ---- query fragments (B operand): column = this lane's row, k-slot = channels 16 s + 8 h
-    bf16x8 qf[2][8];
-    long long out_row[2];
-    bool row_ok[2];
+    bf16x8 qf[NB][8];
+    long long out_row[NB];
+    bool row_ok[NB];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int rr = row0 + wave * 64 + nb * 32 + col;
+    for (int nb = 0; nb < NB; ++nb) {
+        const int rr = row0 + wave * kRowsPerWave + nb * 32 + col;
         row_ok[nb] = rr < rows_b;
         const int sample = s0 + (row_ok[nb] ? rr : 0) / p.G;
         const int head = j * p.G + (row_ok[nb] ? rr : 0) % p.G;
@@ -119,8 +124,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     // other at the end of the iteration (small problems, not worth the registers).
     constexpr bool kPrefetch = (kTasks == 1);
     uint4 stage[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        stage[e] = make_uint4(0, 0, 0, 0);
     auto issue_loads = [&](int tb, int k) __attribute__((always_inline)) {
         const int task = tid + k * kThreads;
+        if (task >= 256)
+            return;
         const int piece = task & 15;
         const int grp = (task >> 4) & 7;
         const bool is_v = task >= 128;
@@ -136,6 +146,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
         const int task = tid + k * kThreads;
         const int piece = task & 15;
         const int grp = (task >> 4) & 7;
+        if (task >= 256)
+            return;
         if (task < 128) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -161,13 +173,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
         }
     };
 
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
-    floatx16 o[4][2];
+    float m_run[NB], l_run[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        m_run[nb] = -INFINITY;
+        l_run[nb] = 0.f;
+    }
+    floatx16 o[4][NB];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 o[db][nb][i] = 0.f;
@@ -182,11 +198,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
             issue_loads(tb + kTileN, 0);
 
         // ---- S^T = K Q^T : [64 tokens] x [64 rows] ------------------------------------------------
-        floatx16 sacc[2][2];
+        floatx16 sacc[2][NB];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
                     sacc[mb][nb][i] = 0.f;
@@ -196,28 +212,37 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
             for (int mb = 0; mb < 2; ++mb) {
                 const bf16x8 kf = as_bf16x8(ksm[buf][32 * mb + col][2 * s + h]);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
+                for (int nb = 0; nb < NB; ++nb)
                     sacc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][s], sacc[mb][nb], 0, 0, 0);
             }
         }
 
         // ---- online softmax, lane-local per row ---------------------------------------------------
-        bf16x8 pf[2][4];
+        // Scores stay unscaled in the accumulator; the scale is folded into the exponent:
+        // p = 2^(s * scale - m).  Only the last tile of a split can be ragged.
+        const bool full = tb + kTileN <= t1;
+        bf16x8 pf[NB][4];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
+            if (!full) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        // accumulator register i of lane-half h is token 32 mb + 8 (i/4) + 4 h + i%4
+                        const int t = tb + 32 * mb + 8 * (i >> 2) + 4 * h + (i & 3);
+                        if (t >= t1)
+                            sacc[mb][nb][i] = -INFINITY;
+                    }
+            }
             float tmax = -INFINITY;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    // accumulator register i of lane-half h is token 32 mb + 8 (i/4) + 4 h + i%4
-                    const int t = tb + 32 * mb + 8 * (i >> 2) + 4 * h + (i & 3);
-                    const float s2 = t < t1 ? sacc[mb][nb][i] * p.scale_log2 : -INFINITY;
-                    sacc[mb][nb][i] = s2;
-                    tmax = fmaxf(tmax, s2);
-                }
+                for (int i = 0; i < 16; ++i)
+                    tmax = fmaxf(tmax, sacc[mb][nb][i]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float m_new = fmaxf(m_run[nb], tmax);
+            const float m_new = fmaxf(m_run[nb], tmax * p.scale_log2);
             const float corr = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
             m_run[nb] = m_new;
             float psum = 0.f;
@@ -228,7 +253,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
                     float pv[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        pv[e] = __builtin_amdgcn_exp2f(sacc[mb][nb][8 * u + e] - m_new);
+                        pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[mb][nb][8 * u + e], p.scale_log2, -m_new));
                         psum += pv[e];
                     }
                     uint4 pu;
@@ -256,7 +281,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
                 const int ch = 32 * db + col;
                 const bf16x8 vf = as_bf16x8(vsm[buf][ch][(2 * ks + h) ^ ((ch >> 3) & 7)]);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
+                for (int nb = 0; nb < NB; ++nb)
                     o[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][ks], o[db][nb], 0, 0, 0);
             }
         }
@@ -272,7 +297,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
 
     // ---- write the partial state ------------------------------------------------------------------
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
         const float l = l_run[nb] + __shfl_xor(l_run[nb], 32);
         if (!row_ok[nb])
             continue;
@@ -295,12 +320,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
 template <int WAVES>
 hipError_t launch_waves(const AttnParams& p, hipStream_t s)
 {
-    const int rowtiles = (p.max_spp * p.G + 64 * WAVES - 1) / (64 * WAVES);
+    constexpr int kBlockRows = 32 * WAVES;
+    const int rowtiles = (p.max_spp * p.G + kBlockRows - 1) / kBlockRows;
     const dim3 grid(p.num_prefix_splits, rowtiles, p.B * p.Hkv);
     if (p.page_size)
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, true>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, 1, true>), grid, dim3(WAVES * 64), 0, s, p);
     else
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, false>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, 1, false>), grid, dim3(WAVES * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -312,7 +338,8 @@ bool prefix_mfma_supported(const AttnParams& p)
            (long long)p.B * p.Hkv <= 65535;
 }
 
-// Rows per workgroup used for a problem with `rows` query rows per (prompt, KV head).
+// Rows per workgroup used for a problem with `rows` query rows per (prompt, KV head):
+// 32 rows per wavefront, 2 to 8 wavefronts.
 int prefix_mfma_block_rows(int rows)
 {
     return rows > 128 ? 256 : rows > 64 ? 128 : 64;
@@ -322,11 +349,10 @@ hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s)
 {
     if (p.num_prefix_splits <= 0)
         return hipSuccess;
-    const int rows = p.max_spp * p.G;
-    switch (prefix_mfma_block_rows(rows)) {
-    case 256: return launch_waves<4>(p, s);
-    case 128: return launch_waves<2>(p, s);
-    default: return launch_waves<1>(p, s);
+    switch (prefix_mfma_block_rows(p.max_spp * p.G)) {
+    case 256: return launch_waves<8>(p, s);
+    case 128: return launch_waves<4>(p, s);
+    default: return launch_waves<2>(p, s);
     }
 }
 

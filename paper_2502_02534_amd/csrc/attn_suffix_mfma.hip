@@ -45,12 +45,15 @@ __device__ __forceinline__ uint32_t dword(const uint4& v, int k)
     return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Two floats to packed bf16 (round to nearest even): one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    const f32x2 v = {lo, hi};
+    const bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<const uint32_t*>(&r);
 }
 
 template <bool PAGED>
@@ -66,8 +69,10 @@ __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int
     const long long total = (long long)p.N * p.Hkv * nc;
     if (item >= total)
         return;
-    const int chunk = (int)(item % nc);
-    const int j = (int)((item / nc) % p.Hkv);
+    // KV head fastest: the waves of a workgroup (and neighbouring workgroups) read the heads of
+    // the same tokens at the same time, i.e. one contiguous stretch of the [token][head][D] cache
+    const int j = (int)(item % p.Hkv);
+    const int chunk = (int)((item / p.Hkv) % nc);
     const int n = (int)(item / ((long long)nc * p.Hkv));
     const int Ls = p.suffix_lens[n];
     const int t0 = chunk * p.suffix_chunk_tokens;
@@ -153,7 +158,8 @@ __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int
                 sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], sacc[blk], 0, 0, 0);
             }
         }
-        // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c
+        // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c;
+        // scores stay unscaled, the scale is folded into the exponent: p = 2^(s * scale - m)
         float sv[8];
         float tmax = -INFINITY;
 #pragma unroll
@@ -161,19 +167,18 @@ __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int t = tb + 16 * blk + 4 * r + i;
-                const float s2 = t < t1 ? sacc[blk][i] * p.scale_log2 : -INFINITY;
-                sv[4 * blk + i] = s2;
-                tmax = fmaxf(tmax, s2);
+                sv[4 * blk + i] = t < t1 ? sacc[blk][i] : -INFINITY;
+                tmax = fmaxf(tmax, sv[4 * blk + i]);
             }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);  // finite: the tile holds at least one valid token
+        const float m_new = fmaxf(m_run, tmax * p.scale_log2);  // finite: the tile holds a valid token
         const float corr = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
         float psum = 0.f;
         float pv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            pv[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
+            pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[i], p.scale_log2, -m_new));
             psum += pv[i];
         }
         l_run = l_run * corr + psum;

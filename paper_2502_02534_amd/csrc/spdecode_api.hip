@@ -3,6 +3,7 @@
 #include "spd_internal.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 namespace {
 
@@ -69,16 +70,22 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
     } else {
         pl->prefix_split_tokens = part_tokens(max_prefix, 256, 64, 64);
     }
+#ifdef SPD_TUNING
+    if (const char* e = getenv("SPD_TUNE_PREFIX_SPLIT")) pl->prefix_split_tokens = atoi(e);
+#endif
     pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
     {
         // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..512 tokens
         const long long pairs = (long long)d->num_samples * d->num_kv_heads;
-        const long long want_chunks = (4096 + pairs - 1) / pairs;
+        const long long want_chunks = (2048 + pairs - 1) / pairs;
         long long t = (max_suffix + want_chunks - 1) / want_chunks;
         t = (t + 63) / 64 * 64;
         if (t < 64) t = 64;
         if (t > 512) t = 512;
         if (max_suffix > t * 64) t = part_tokens(max_suffix, 64, 64, 64);
+#ifdef SPD_TUNING
+        if (const char* e = getenv("SPD_TUNE_SUFFIX_CHUNK")) t = atoi(e);
+#endif
         pl->suffix_chunk_tokens = (int)t;
     }
     pl->num_suffix_chunks = (int)((max_suffix + pl->suffix_chunk_tokens - 1) / pl->suffix_chunk_tokens);
