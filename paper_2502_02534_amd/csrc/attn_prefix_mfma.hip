@@ -7,7 +7,7 @@
 // column block of the transposed product), two wavefronts share a SIMD so that one's
 // softmax overlaps the other's MFMAs.  K and V tiles of 64 tokens are loaded
 // cooperatively, 16 bytes per lane with 16 adjacent lanes per 256-byte row, and
-// double-buffered in LDS:
+// triple-buffered in LDS:
 //   K  row-major [token][channel] (padded rows), read as the A operand of
 //      S^T = K Q^T          (v_mfma_f32_32x32x16_bf16, B = query rows, in registers)
 //   V  transposed on the way in: a lane loads the same 8-channel slice of 8 token rows,
@@ -18,6 +18,8 @@
 // the accumulator rescale are lane-local.  The running state is the deferred-division
 // form of the paper's online-softmax recurrence (App., attn task 2).
 #include "spd_internal.h"
+
+#include <type_traits>
 
 namespace spd {
 namespace {
@@ -63,8 +65,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     constexpr int kThreads = WAVES * 64;
     constexpr int kRowsPerWave = 32 * NB;
     constexpr int kTasks = (256 + kThreads - 1) / kThreads;  // load tasks per thread per tile
-    __shared__ uint4 ksm[2][kTileN][kKRowU4];
-    __shared__ uint4 vsm[2][kD][kVRowU4];
+    // With 512 threads a tile needs only half of them: threads 0..255 carry the even tiles and
+    // threads 256..511 the odd ones, so every load has two iterations to arrive (twice the
+    // bytes in flight for the same registers).
+    constexpr bool kDeep = (kThreads == 512);
+    __shared__ uint4 ksm[3][kTileN][kKRowU4];
+    __shared__ uint4 vsm[3][kD][kVRowU4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -119,60 +125,56 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     // ---- cooperative tile loads ---------------------------------------------------------------
     // task 0..127: K rows 8 (task/16) .. + 7, piece task % 16
     // task 128..255: V fragment (task-128)/16, piece (task-128) % 16
-    // With four waves every thread has exactly one task and its 8 loads are issued a whole
-    // tile ahead; with fewer waves the tasks of a thread are loaded and stored one after the
-    // other at the end of the iteration (small problems, not worth the registers).
-    constexpr bool kPrefetch = (kTasks == 1);
-    uint4 stage[8];
+    // The 8 loads of a task are issued two tiles ahead of their use and parked in registers.
+    uint4 stage[kTasks][8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        stage[e] = make_uint4(0, 0, 0, 0);
-    auto issue_loads = [&](int tb, int k) __attribute__((always_inline)) {
-        const int task = tid + k * kThreads;
-        if (task >= 256)
-            return;
-        const int piece = task & 15;
-        const int grp = (task >> 4) & 7;
-        const bool is_v = task >= 128;
+    for (int k = 0; k < kTasks; ++k)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int tl = is_v ? frag_token(grp, e) : 8 * grp + e;
-            const int t = min(tb + tl, t1 - 1);
-            const long long idx = row_index(t, piece);
-            stage[e] = is_v ? vg[idx] : kg[idx];
-        }
-    };
-    auto store_tile = [&](int buf, int k) __attribute__((always_inline)) {
-        const int task = tid + k * kThreads;
-        const int piece = task & 15;
-        const int grp = (task >> 4) & 7;
-        if (task >= 256)
-            return;
-        if (task < 128) {
+        for (int e = 0; e < 8; ++e)
+            stage[k][e] = make_uint4(0, 0, 0, 0);
+    auto issue_loads = [&](int tb) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                ksm[buf][8 * grp + e][piece] = stage[e];
-        } else {
+        for (int k = 0; k < kTasks; ++k) {
+            const int task = kDeep ? (tid & 255) : tid + k * kThreads;
+            if (task < 256) {
+                const int piece = task & 15;
+                const int grp = (task >> 4) & 7;
+                const bool is_v = task >= 128;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-                uint4 f;
-                f.x = __builtin_amdgcn_perm(dword(stage[1], i >> 1), dword(stage[0], i >> 1), sel);
-                f.y = __builtin_amdgcn_perm(dword(stage[3], i >> 1), dword(stage[2], i >> 1), sel);
-                f.z = __builtin_amdgcn_perm(dword(stage[5], i >> 1), dword(stage[4], i >> 1), sel);
-                f.w = __builtin_amdgcn_perm(dword(stage[7], i >> 1), dword(stage[6], i >> 1), sel);
-                // channel 8 piece + i; fragment slot swizzled by the channel group
-                vsm[buf][8 * piece + i][grp ^ (piece & 7)] = f;
+                for (int e = 0; e < 8; ++e) {
+                    const int tl = is_v ? frag_token(grp, e) : 8 * grp + e;
+                    const int t = min(tb + tl, t1 - 1);
+                    const long long idx = row_index(t, piece);
+                    stage[k][e] = is_v ? vg[idx] : kg[idx];
+                }
             }
         }
     };
-    auto load_and_store_all = [&](int tb, int buf) __attribute__((always_inline)) {
+    auto store_tile = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
         for (int k = 0; k < kTasks; ++k) {
-            issue_loads(tb, k);
-            store_tile(buf, k);
+            const int task = kDeep ? (tid & 255) : tid + k * kThreads;
+            const int piece = task & 15;
+            const int grp = (task >> 4) & 7;
+            if (task < 128) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    ksm[buf][8 * grp + e][piece] = stage[k][e];
+            } else if (task < 256) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                    uint4 f;
+                    f.x = __builtin_amdgcn_perm(dword(stage[k][1], i >> 1), dword(stage[k][0], i >> 1), sel);
+                    f.y = __builtin_amdgcn_perm(dword(stage[k][3], i >> 1), dword(stage[k][2], i >> 1), sel);
+                    f.z = __builtin_amdgcn_perm(dword(stage[k][5], i >> 1), dword(stage[k][4], i >> 1), sel);
+                    f.w = __builtin_amdgcn_perm(dword(stage[k][7], i >> 1), dword(stage[k][6], i >> 1), sel);
+                    // channel 8 piece + i; fragment slot swizzled by the channel group
+                    vsm[buf][8 * piece + i][grp ^ (piece & 7)] = f;
+                }
+            }
         }
     };
-
     float m_run[NB], l_run[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -187,41 +189,59 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 o[db][nb][i] = 0.f;
+    floatx16 sacc[2][NB];
+    bf16x8 pf[NB][4];  // P of the previous tile, B-operand layout
 
-    load_and_store_all(t0, 0);
-    __syncthreads();
-
-    int buf = 0;
-    for (int tb = t0; tb < t1; tb += kTileN, buf ^= 1) {
-        const bool more = tb + kTileN < t1;
-        if (kPrefetch && more)
-            issue_loads(tb + kTileN, 0);
-
-        // ---- S^T = K Q^T : [64 tokens] x [64 rows] ------------------------------------------------
-        floatx16 sacc[2][NB];
+    // One MFMA region: the scores of tile `kbuf` (S^T = K Q^T, 16 MFMAs per column block) and,
+    // interleaved with them, O^T += V^T P^T for the previous tile `vbuf` (16 more).  The two
+    // products are independent, so their accumulator chains hide each other's latency; the
+    // scheduler is asked for a fragment pipeline (a few LDS reads up front, then one read per
+    // MFMA) so that no MFMA waits for the read issued right before it.
+    auto mfma_region = [&](auto do_qk, auto do_pv, int kbuf, int vbuf) __attribute__((always_inline)) {
+        constexpr bool QK = decltype(do_qk)::value, PV = decltype(do_pv)::value;
+        if (QK) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    sacc[mb][nb][i] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 kf = as_bf16x8(ksm[buf][32 * mb + col][2 * s + h]);
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    sacc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][s], sacc[mb][nb], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        sacc[mb][nb][i] = 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            if (QK) {
+                const int st = k >> 1, mb = k & 1;
+                const bf16x8 kf = as_bf16x8(ksm[kbuf][32 * mb + col][2 * st + h]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    sacc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][st], sacc[mb][nb], 0, 0, 0);
+            }
+            if (PV) {
+                const int ks = k >> 2, db = k & 3;
+                const int ch = 32 * db + col;
+                const bf16x8 vf = as_bf16x8(vsm[vbuf][ch][(2 * ks + h) ^ ((ch >> 3) & 7)]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    o[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][ks], o[db][nb], 0, 0, 0);
             }
         }
+        constexpr int kFrags = (QK ? 16 : 0) + (PV ? 16 : 0);
+        constexpr int kAhead = 6;
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+        for (int k = 0; k < kFrags - kAhead; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead * NB, 0);
+    };
 
-        // ---- online softmax, lane-local per row ---------------------------------------------------
-        // Scores stay unscaled in the accumulator; the scale is folded into the exponent:
-        // p = 2^(s * scale - m).  Only the last tile of a split can be ragged.
-        const bool full = tb + kTileN <= t1;
-        bf16x8 pf[NB][4];
+    // Online softmax of the scores in `sacc` (lane-local per row): updates (m, l), rescales O
+    // (which already holds every earlier tile) and leaves P in `pf`.  Scores stay unscaled in
+    // the accumulator; the scale is folded into the exponent: p = 2^(s * scale - m).
+    auto softmax_tile = [&](int tb) __attribute__((always_inline)) {
+        const bool full = tb + kTileN <= t1;  // only the last tile of a split can be ragged
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (!full) {
@@ -272,28 +292,52 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
                         o[db][nb][i] *= corr;
             }
         }
+    };
 
-        // ---- O^T += V^T P^T : [128 channels] x [64 rows] ------------------------------------------
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const int ch = 32 * db + col;
-                const bf16x8 vf = as_bf16x8(vsm[buf][ch][(2 * ks + h) ^ ((ch >> 3) & 7)]);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    o[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][ks], o[db][nb], 0, 0, 0);
-            }
+    // Pipeline over tiles (three LDS buffers).  Iteration `it` issues the global loads of tile
+    // it+1, runs one MFMA region (scores of tile `it` together with P V of tile it-1), then the
+    // softmax of tile `it` on the vector ALU (which the other wavefront of the SIMD overlaps
+    // with its own MFMA region), and parks tile it+1 in LDS.  One barrier per tile.
+    const int ntiles = (t1 - t0 + kTileN - 1) / kTileN;
+    const std::true_type yes{};
+    const std::false_type no{};
+    const int half = kDeep ? (tid >> 8) : 0;  // which tiles this thread carries (deep mode)
+    auto mine = [&](int tile) { return !kDeep || (tile & 1) == half; };
+    if (mine(0))
+        issue_loads(t0);
+    if (kDeep && mine(1) && ntiles > 1)
+        issue_loads(t0 + kTileN);
+    if (mine(0))
+        store_tile(0);
+    if (!kDeep && ntiles > 1)
+        issue_loads(t0 + kTileN);
+    if (kDeep && mine(2) && ntiles > 2)
+        issue_loads(t0 + 2 * kTileN);
+    __syncthreads();
+    mfma_region(yes, no, 0, 0);
+    softmax_tile(t0);
+    if (ntiles > 1) {
+        if (mine(1))
+            store_tile(1);
+        __syncthreads();
+    }
+    for (int it = 1; it < ntiles; ++it) {
+        const int tb = t0 + it * kTileN;
+        if (kDeep) {
+            if (mine(it + 2) && it + 2 < ntiles)
+                issue_loads(tb + 2 * kTileN);
+        } else if (it + 1 < ntiles) {
+            issue_loads(tb + kTileN);
         }
-
-        if (more) {
-            if (kPrefetch)
-                store_tile(buf ^ 1, 0);
-            else
-                load_and_store_all(tb + kTileN, buf ^ 1);
+        mfma_region(yes, yes, it % 3, (it - 1) % 3);
+        softmax_tile(tb);
+        if (it + 1 < ntiles) {
+            if (mine(it + 1))
+                store_tile((it + 1) % 3);
             __syncthreads();
         }
     }
+    mfma_region(no, yes, 0, (ntiles - 1) % 3);
 
     // ---- write the partial state ------------------------------------------------------------------
 #pragma unroll
