@@ -426,6 +426,7 @@ constexpr int kSliceMax = 8 * kIter;      // elements per workgroup: 8 float4 pe
 constexpr int kMaxSlices = 16;
 constexpr int kSegPerSlice = kSliceMax / kSeg;  // 64
 constexpr int kCandCap = 4096;
+constexpr int kPubBins = 1024;   // histogram bins a slice publishes (64 octaves below its maximum)
 static_assert(kMaxSlices * kSegPerSlice <= kMaxSegments, "segment table too small");
 
 struct SliceStat {
@@ -605,7 +606,7 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
         auto add = [&](float xq) {
             const float t = xq * rc.c16;
             const float kf = floorf(t);
-            const int b = bin_below(kf_loc, kf);
+            const int b = min(bin_below(kf_loc, kf), kPubBins - 1);
             // mass relative to the bin's own reference 2^(kf/16): 2^(frac/16) in [1, 2^(1/16))
             const unsigned q = (unsigned)(__builtin_amdgcn_exp2f((t - kf) * 0.0625f) * 32768.f + 0.5f);
             atomicAdd(&hist[b], q);
@@ -618,15 +619,11 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
         if (tid == 0)
             for (int k = 0; k < g.ntail; ++k)
                 add(x[g.v4end + k]);
-        for (int o = 32; o > 0; o >>= 1)
-            bmax = max(bmax, __shfl_xor(bmax, o));
-        __syncthreads();  // red_i reuse below; histogram complete
-        if (lane == 0)
-            red_i[wave] = bmax;
-        __syncthreads();
-        for (int w = 0; w < kWaves; ++w)
-            nbins = max(nbins, red_i[w] + 1);
-        for (int b = tid; b < nbins; b += kBlock)
+        (void)bmax;
+        __syncthreads();  // histogram complete
+        // a fixed number of bins is written so that the reader needs nothing else to fetch them
+        nbins = kPubBins;
+        for (int b = tid; b < kPubBins; b += kBlock)
             W.hist[(size_t)slice * kBins + b] = hist[b];
     }
     if (tid == 0) {
@@ -667,6 +664,15 @@ __global__ __launch_bounds__(kBlock) void sampler_cut_kernel(SamplerParams sp, c
     const bool greedy = (T == 0.f);
     const float top_p = sp.top_p[r];
     const bool cut = !greedy && top_p < 1.f;
+    // everything this kernel reads from memory is requested up front, in one round
+    constexpr int kPerThread = kMaxSlices * kPubBins / kBlock;
+    unsigned qv[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+        const int it = tid + u * kBlock;
+        const int sl = it / kPubBins, b = it % kPubBins;
+        qv[u] = (cut && sl < slices) ? W.hist[(size_t)sl * kBins + b] : 0u;
+    }
     if (tid < slices) {
         const SliceStat* st = stat_at(W, tid);
         L.smax[tid] = st->max_x;
@@ -697,26 +703,14 @@ __global__ __launch_bounds__(kBlock) void sampler_cut_kernel(SamplerParams sp, c
         // bin b of slice s is bin b + shift[s] of the row; mass = q 2^-15 2^(-bin/16) relative to
         // the reference of the row maximum's bin.  Stored mirrored (most probable bin last) for
         // pick_bin.
-        // (loads are issued four at a time; a load-use-load chain would pay the memory latency
-        // once per trip)
-        const int items = slices * nb_max;
-        for (int base = tid; base < items; base += 4 * kBlock) {
-            unsigned qv[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int it = base + u * kBlock;
-                const int sl = it / nb_max, b = it - sl * nb_max;
-                qv[u] = (it < items && b < L.snb[sl]) ? W.hist[(size_t)sl * kBins + b] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (qv[u]) {
-                    const int it = base + u * kBlock;
-                    const int sl = it / nb_max, b = it - sl * nb_max;
-                    const int rb = min(b + L.shift[sl], kBins - 1);
-                    // q 2^-15 2^(-rb/16): sixteenth roots from a table, the rest is an exponent shift
-                    atomicAdd(&L.hist[kBins - 1 - rb], ldexp((double)qv[u] * kRoot16[rb & 15], -15 - (rb >> 4)));
-                }
+        for (int u = 0; u < kPerThread; ++u) {
+            if (qv[u]) {
+                const int it = tid + u * kBlock;
+                const int sl = it / kPubBins, b = it % kPubBins;
+                const int rb = min(b + L.shift[sl], kBins - 1);
+                // q 2^-15 2^(-rb/16): sixteenth roots from a table, the rest is an exponent shift
+                atomicAdd(&L.hist[kBins - 1 - rb], ldexp((double)qv[u] * kRoot16[rb & 15], -15 - (rb >> 4)));
             }
         }
         __syncthreads();
@@ -771,6 +765,12 @@ __global__ __launch_bounds__(kBlock) void sampler_mass_kernel(SamplerParams sp, 
     rs.c_hi = rc.c_hi;
     rs.c_lo = rc.c_lo;
     const int lo = cutv.lo, hi = cutv.hi;
+    // Bin tests without forming the bin: with t = x c16, bin(x) < lo  <=>  floor(t) > kf_row - lo
+    // <=>  t >= kf_row - lo + 1 (both sides of the middle inequality are integers); likewise
+    // bin(x) <= hi  <=>  t >= kf_row - hi.  The clamps of the bin only matter at the ends:
+    // lo == kBins keeps everything, hi == kBins - 1 makes every remaining element a candidate.
+    const float t_above = lo >= kBins ? -INFINITY : cutv.kf_row - (float)lo + 1.f;
+    const float t_cand = hi >= kBins - 1 ? -INFINITY : cutv.kf_row - (float)hi;
 
     float xv[32];
     SPD_LOAD_SLICE(xv, x, g, tid)
@@ -788,16 +788,18 @@ __global__ __launch_bounds__(kBlock) void sampler_mass_kernel(SamplerParams sp, 
                 continue;
             const float p = prob(xq, rs);
             all32 += p;
-            const int b = bin_below(cutv.kf_row, bin_coord(xq, rc.c16));
-            if (b < lo)
+            const float t = xq * rc.c16;
+            if (t >= t_above)
                 s_above += p;
-            else if (b <= hi)
+            else if (t >= t_cand)
                 ++ncand;
         }
-        const double wa = wave_sum_f64((double)s_above);
+        // 256 fp32 terms per segment; the segment sums are widened before they are combined
+        for (int o = 32; o > 0; o >>= 1)
+            s_above += __shfl_xor(s_above, o);
         if (lane == 0) {
-            W.seg[(size_t)slice * kSegPerSlice + j * kWaves + wave] = wa;
-            above += wa;
+            W.seg[(size_t)slice * kSegPerSlice + j * kWaves + wave] = (double)s_above;
+            above += (double)s_above;
         }
     }
     double mass = (double)all32;
@@ -844,8 +846,8 @@ __global__ __launch_bounds__(kBlock) void sampler_mass_kernel(SamplerParams sp, 
             const float xq = xv[q];
             if (xq == -INFINITY)
                 continue;
-            const int b = bin_below(cutv.kf_row, bin_coord(xq, rc.c16));
-            if (b >= lo && b <= hi) {
+            const float t = xq * rc.c16;
+            if (t < t_above && t >= t_cand) {
                 if (pos < (unsigned)kCandCap)
                     W.cand[pos] = (unsigned long long)__float_as_uint(xq) |
                                   ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32);
