@@ -20,19 +20,20 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-constexpr int kMergeThreads = 256;
+#ifndef SPD_MERGE_THREADS
+#define SPD_MERGE_THREADS 256
+#endif
+constexpr int kMergeThreads = SPD_MERGE_THREADS;
 constexpr int kMaxSlots = 128;   // prefix splits + suffix chunks (each at most 64)
 
 // One workgroup merges kMergeThreads / (D/4) rows; a thread owns 4 channels of one row.
 // Step 1 puts every valid partial's (m, l) in LDS, step 2 turns them into weights
-// 2^(m_i - m) (0 for empty partials) and the row's m and l, step 3 streams the accumulators
-// with eight independent 16-byte loads in flight per thread.
+// 2^(m_i - m) (0 for empty partials) and the row's m and l, step 3 combines the accumulators,
+// whose loads (up to 32 independent 16-byte loads per thread) were issued before step 1.
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p, int tpr /* threads per row */)
 {
     __shared__ float2 ml[kMergeThreads / 8][kMaxSlots];   // at most 32 rows per block (D = 32)
     __shared__ float wgt[kMergeThreads / 8][kMaxSlots];
-    __shared__ int slot_of[kMergeThreads / 8][kMaxSlots];
-    __shared__ int nvalid[kMergeThreads / 8];
     __shared__ float row_m[kMergeThreads / 8], row_l[kMergeThreads / 8];
 
     const int rows_per_block = kMergeThreads / tpr;
@@ -51,11 +52,21 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
         ns = p.suffix_chunk_tokens > 0 ? (Ls + p.suffix_chunk_tokens - 1) / p.suffix_chunk_tokens : 0;
     }
     const int cnt = np + ns;
-    for (int i = c; i < cnt; i += tpr) {
-        const int slot = i < np ? i : p.num_prefix_splits + (i - np);
-        slot_of[r_in][i] = slot;
-        ml[r_in][i] = p.part_ml[(long long)slot * total + row];
+    const bool ch_ok = row_ok && 4 * c < p.D;
+    const float* base = p.part_acc + part_index(p, row_ok ? row : 0, 0) * p.D + 4 * c;
+    auto slot_at = [&](int i) { return i < np ? i : p.num_prefix_splits + (i - np); };
+    // The first batch of accumulator loads does not need the weights: it is issued together
+    // with the (m, l) loads so that both round trips overlap.
+    constexpr int kBatch = 32;
+    float4 v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ch_ok && u < cnt)
+            v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_at(u) * p.D);
     }
+    for (int i = c; i < cnt; i += tpr)
+        ml[r_in][i] = p.part_ml[part_index(p, row, slot_at(i))];
     __syncthreads();
     if (c == 0) {
         float m = -INFINITY;
@@ -63,39 +74,35 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
             m = fmaxf(m, ml[r_in][i].x);
         float l = 0.f;
         for (int i = 0; i < cnt; ++i) {
-            const float2 v = ml[r_in][i];
-            const float w = v.y > 0.f ? __builtin_amdgcn_exp2f(v.x - m) : 0.f;
+            const float2 mv = ml[r_in][i];
+            const float w = mv.y > 0.f ? __builtin_amdgcn_exp2f(mv.x - m) : 0.f;
             wgt[r_in][i] = w;
-            l = fmaf(v.y, w, l);
+            l = fmaf(mv.y, w, l);
         }
         row_m[r_in] = m;
         row_l[r_in] = l;
-        nvalid[r_in] = cnt;
     }
     __syncthreads();
-    if (!row_ok || 4 * c >= p.D)
+    if (!ch_ok)
         return;
     const float l = row_l[r_in];
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    const float* base = p.part_acc + row * p.D + 4 * c;
-    const long long slot_stride = total * p.D;
-    for (int i0 = 0; i0 < cnt; i0 += 8) {
-        float4 v[8];
-        float w[8];
+    for (int i0 = 0; i0 < cnt; i0 += kBatch) {
+        if (i0 > 0) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = i0 + u;
-            w[u] = i < cnt ? wgt[r_in][i] : 0.f;
-            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (w[u] != 0.f)
-                v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_of[r_in][i] * slot_stride);
+            for (int u = 0; u < kBatch; ++u) {
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i0 + u < cnt)
+                    v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_at(i0 + u) * p.D);
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            acc.x = fmaf(v[u].x, w[u], acc.x);
-            acc.y = fmaf(v[u].y, w[u], acc.y);
-            acc.z = fmaf(v[u].z, w[u], acc.z);
-            acc.w = fmaf(v[u].w, w[u], acc.w);
+        for (int u = 0; u < kBatch; ++u) {
+            const float w = i0 + u < cnt ? wgt[r_in][i0 + u] : 0.f;
+            acc.x = fmaf(v[u].x, w, acc.x);
+            acc.y = fmaf(v[u].y, w, acc.y);
+            acc.z = fmaf(v[u].z, w, acc.z);
+            acc.w = fmaf(v[u].w, w, acc.w);
         }
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;

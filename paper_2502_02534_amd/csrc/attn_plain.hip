@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnParams p, int slot0,
             }
         }
     }
-    const long long prow = (long long)(slot0 + part) * p.N * p.Hq + row;
+    const long long prow = part_index(p, row, slot0 + part);
     float* dst = p.part_acc + prow * D;
 #pragma unroll
     for (int i = 0; i < kMaxChanPerLane; ++i) {

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
         const float l = l_run[nb] + __shfl_xor(l_run[nb], 32);
         if (!row_ok[nb])
             continue;
-        const long long prow = (long long)split * p.N * p.Hq + out_row[nb];
+        const long long prow = part_index(p, out_row[nb], split);
         if (h == 0)
             p.part_ml[prow] = make_float2(m_run[nb], l);
         float* dst = p.part_acc + prow * kD;

@@ -227,14 +227,14 @@ __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int
     l_run += __shfl_xor(l_run, 32);
 
     // ---- write the partial state ----------------------------------------------------------------
-    const long long prow0 = ((long long)(slot0 + chunk) * p.N + n) * p.Hq + (long long)j * G;
+    const long long row0 = (long long)n * p.Hq + (long long)j * G;  // first of the G output rows
     if (r == 0 && c < G)
-        p.part_ml[prow0 + c] = make_float2(m_run, l_run);
+        p.part_ml[part_index(p, row0 + c, slot0 + chunk)] = make_float2(m_run, l_run);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int g = 4 * r + i;
         if (g < G) {
-            float* dst = p.part_acc + (prow0 + g) * kD + 8 * c;
+            float* dst = p.part_acc + part_index(p, row0 + g, slot0 + chunk) * kD + 8 * c;
 #pragma unroll
             for (int k = 0; k < 8; ++k)
                 dst[k] = o[k][i];

@@ -33,8 +33,9 @@ struct AttnParams {
     long long max_suffix_len;
     int prefix_split_tokens, num_prefix_splits;
     int suffix_chunk_tokens, num_suffix_chunks;
-    float* part_acc;  // [slots][N*Hq][D]
-    float2* part_ml;  // [slots][N*Hq]  (m, l)
+    int num_slots;    // prefix splits + suffix chunks
+    float* part_acc;  // [N*Hq][slots][D]: a row's partial states are contiguous for the merge
+    float2* part_ml;  // [N*Hq][slots]  (m, l)
     void* out;
     float* lse;
 };
@@ -47,6 +48,12 @@ struct SamplerParams {
     const float* uniforms;
     int* tokens;
 };
+
+// Index of the partial state of output row `row` (= n * Hq + h) in slot `slot`.
+__device__ __forceinline__ long long part_index(const AttnParams& p, long long row, int slot)
+{
+    return row * p.num_slots + slot;
+}
 
 // Prompt that owns sample n (sample_indptr is sorted, B >= 1).
 __device__ __forceinline__ int prompt_of_sample(const int* __restrict__ indptr, int B, int n)

@@ -200,6 +200,7 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
     p.num_prefix_splits = pl.num_prefix_splits;
     p.suffix_chunk_tokens = pl.suffix_chunk_tokens;
     p.num_suffix_chunks = pl.num_suffix_chunks;
+    p.num_slots = pl.num_prefix_splits + pl.num_suffix_chunks;
     p.part_acc = (float*)workspace;
     p.part_ml = (float2*)((char*)workspace + pl.acc_bytes);
     p.out = out;
