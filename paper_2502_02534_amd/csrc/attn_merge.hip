@@ -20,10 +20,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-#ifndef SPD_MERGE_THREADS
-#define SPD_MERGE_THREADS 256
-#endif
-constexpr int kMergeThreads = SPD_MERGE_THREADS;
+constexpr int kMergeThreads = 256;
 constexpr int kMaxSlots = 128;   // prefix splits + suffix chunks (each at most 64)
 
 // One workgroup merges kMergeThreads / (D/4) rows; a thread owns 4 channels of one row.

@@ -3,45 +3,51 @@
 // tile instead of once per sample.
 //
 // Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix).
-// A query row is (sample, head in group); each wavefront owns 32 rows (one 32-wide
-// column block of the transposed product), two wavefronts share a SIMD so that one's
-// softmax overlaps the other's MFMAs.  K and V tiles of 64 tokens are loaded
-// cooperatively, 16 bytes per lane with 16 adjacent lanes per 256-byte row, and
-// triple-buffered in LDS:
-//   K  row-major [token][channel] (padded rows), read as the A operand of
-//      S^T = K Q^T          (v_mfma_f32_32x32x16_bf16, B = query rows, in registers)
-//   V  transposed on the way in: a lane loads the same 8-channel slice of 8 token rows,
-//      transposes the 8x8 block with byte permutes and stores 8 token-contiguous
-//      fragments, read as the A operand of
-//      O^T += V^T P^T       (B = P, which is the S^T accumulator itself, repacked to bf16)
-// Every lane owns one query row in both products, so the online-softmax statistics and
-// the accumulator rescale are lane-local.  The running state is the deferred-division
-// form of the paper's online-softmax recurrence (App., attn task 2).
+// A query row is (sample, head in group); each wavefront owns 32 rows (one 32-wide column
+// block of the transposed products).
+//
+// Data movement.  K and V tiles of 64 tokens go from global memory straight into LDS
+// (global_load_lds_dwordx4, no registers in between), four tiles deep, so two tiles are in
+// flight while one is being used.  Both tiles are row-major [token][256 bytes] without
+// padding; bank conflicts are avoided by an XOR swizzle of the 16-byte pieces of a row,
+// applied on the global side of the copy (lane L of a copy instruction always lands at
+// LDS offset 16 L, but it may fetch any piece).
+//   K  read with ds_read_b128 as the A operand of S^T = K Q^T
+//      (v_mfma_f32_32x32x16_bf16, B = query rows held in registers);
+//   V  read with the transposing ds_read_b64_tr_b16 (each lane receives four tokens of one
+//      channel) as the A operand of O^T += V^T P^T, B = P, which is the S^T accumulator
+//      itself repacked to bf16.
+// The LDS reads are issued by hand (inline assembly) a few fragments ahead of the MFMA that
+// consumes them, with exact lgkmcnt waits; the compiler's own wait insertion would otherwise
+// drain every outstanding copy before any LDS read.
+//
+// Every lane owns one query row in both products, so the online-softmax statistics and the
+// accumulator rescale are lane-local.  The running state is the deferred-division form of the
+// paper's online-softmax recurrence (App., attn task 2).
 #include "spd_internal.h"
 
-#include <type_traits>
+#include <utility>
 
 namespace spd {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-
-constexpr int kD = 128;
-constexpr int kTileN = 64;    // tokens per tile
-constexpr int kKRowU4 = 17;   // K tile row: 16 x 16 B + 16 B pad
-constexpr int kVRowU4 = 9;    // V^T tile row (one channel): 8 fragments x 16 B + 16 B pad
-constexpr int kRowU4 = kD * 2 / 16;
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return *reinterpret_cast<bf16x8*>(&v); }
-
-__device__ __forceinline__ uint32_t dword(const uint4& v, int k)
-{
-    return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
-}
-
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;
+constexpr int kTileN = 64;               // tokens per tile
+constexpr int kStages = 4;               // LDS ring depth
+constexpr int kTileBytes = kTileN * 256;  // one K or V tile
+constexpr int kStageBytes = 2 * kTileBytes;
+constexpr int kRowU4 = kD * 2 / 16;
+constexpr int kAhead = 4;                // LDS fragments in flight ahead of the MFMAs
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return *reinterpret_cast<bf16x8*>(&v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return *reinterpret_cast<bf16x8*>(&v); }
 
 // Two floats to packed bf16 (round to nearest even): one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
@@ -51,26 +57,53 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
     return *reinterpret_cast<const uint32_t*>(&r);
 }
 
-// Token (relative to the tile) of element e (0..7) of V fragment f (0..7).  Fragment
-// f = 2 ks + h feeds k-step ks, lane-half h, and must list the tokens in the order the
-// S^T accumulator hands them to that lane-half: 16 ks + {4h..4h+3, 8+4h..8+4h+3}.
-__device__ __forceinline__ int frag_token(int f, int e)
+// Swizzle of the 16-byte pieces of token row `tok` (within a tile): piece p lives in slot
+// p ^ swz(tok).  Sixteen consecutive rows get sixteen different values (K operand reads: 16
+// lanes, 16 rows, one piece each), and four consecutive rows land in four different 64-byte
+// quarters of the 256-byte bank window (V reads: four rows, up to four neighbouring pieces each).
+__device__ __forceinline__ int swz(int tok) { return ((tok & 3) << 2) | ((tok >> 2) & 3); }
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
-    return 16 * (f >> 1) + 4 * (f & 1) + (e < 4 ? e : e + 4);
+    // vmcnt(N); expcnt and lgkmcnt left alone
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int WAVES, int NB, bool PAGED>
+// One LDS fragment: a K fragment is one ds_read_b128, a V fragment two transposing reads.
+// QK: a = channel step (0..7), b = token block (0..1).  PV: a = token step (0..3), b = channel
+// block (0..3).  When a region holds both products they alternate.
+template <bool QK, bool PV, int K> struct Frag {
+    static constexpr bool both = QK && PV;
+    static constexpr int idx = both ? (K >> 1) : K;
+    static constexpr bool is_pv = both ? ((K & 1) != 0) : PV;
+    static constexpr int a = is_pv ? (idx >> 2) : (idx >> 1);
+    static constexpr int b = is_pv ? (idx & 3) : (idx & 1);
+    static constexpr int ops = is_pv ? 2 : 1;
+};
+template <bool QK, bool PV> constexpr int frag_count() { return (QK ? 16 : 0) + (PV ? 16 : 0); }
+// LDS instructions issued after fragment K while K is the oldest outstanding one
+template <bool QK, bool PV, int K> constexpr int ops_after()
+{
+    int n = 0;
+    for (int j = K + 1; j <= K + kAhead && j < frag_count<QK, PV>(); ++j) {
+        const bool both = QK && PV;
+        const bool is_pv = both ? ((j & 1) != 0) : PV;
+        n += is_pv ? 2 : 1;
+    }
+    return n;
+}
+
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+
+template <int WAVES, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams p)
 {
-    constexpr int kThreads = WAVES * 64;
-    constexpr int kRowsPerWave = 32 * NB;
-    constexpr int kTasks = (256 + kThreads - 1) / kThreads;  // load tasks per thread per tile
-    // With 512 threads a tile needs only half of them: threads 0..255 carry the even tiles and
-    // threads 256..511 the odd ones, so every load has two iterations to arrive (twice the
-    // bytes in flight for the same registers).
-    constexpr bool kDeep = (kThreads == 512);
-    __shared__ uint4 ksm[3][kTileN][kKRowU4];
-    __shared__ uint4 vsm[3][kD][kVRowU4];
+    constexpr int kIPW = 32 / WAVES;  // copy instructions per wave per tile
+    __shared__ uint4 lds[kStages * kStageBytes / 16];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -81,160 +114,183 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     const int b = blockIdx.z / p.Hkv, j = blockIdx.z % p.Hkv;
     const int s0 = p.sample_indptr[b];
     const int rows_b = (p.sample_indptr[b + 1] - s0) * p.G;
-    const int row0 = rowtile * kRowsPerWave * WAVES;
+    const int row0 = rowtile * 32 * WAVES;
     const int Lp = p.prefix_lens[b];
     const int t0 = split * p.prefix_split_tokens;
     const int t1 = min(Lp, t0 + p.prefix_split_tokens);
     if (row0 >= rows_b || t0 >= t1)
         return;
 
-    const uint4* __restrict__ kg = (const uint4*)p.k_prefix;
-    const uint4* __restrict__ vg = (const uint4*)p.v_prefix;
-    const int* __restrict__ pages = PAGED ? p.prefix_pages + p.prefix_indptr[b] : nullptr;
-    const long long start = PAGED ? 0 : p.prefix_indptr[b];
-
-    auto row_index = [&](int t, int piece) -> long long {
-        if (PAGED) {
-            const long long pg = pages[t >> 4];
-            return ((pg * p.Hkv + j) * 16 + (t & 15)) * kRowU4 + piece;
-        }
-        return ((start + t) * p.Hkv + j) * kRowU4 + piece;
-    };
+    const char* __restrict__ kg = (const char*)p.k_prefix;
+    const char* __restrict__ vg = (const char*)p.v_prefix;
+    // the page table is read with scalar loads (uniform index, constant address space)
+    typedef const __attribute__((address_space(4))) int* const_int_ptr;
+    const const_int_ptr pages = PAGED ? (const_int_ptr)(p.prefix_pages + p.prefix_indptr[b]) : nullptr;
+    // byte strides of a token row and byte offset of token 0 of this KV head
+    const long long tok_stride = PAGED ? 256 : (long long)p.Hkv * 256;
+    const long long head_base = PAGED ? (long long)j * 16 * 256 : ((long long)p.prefix_indptr[b] * p.Hkv + j) * 256;
+    const long long page_stride = (long long)p.Hkv * 16 * 256;
 
     // ---- query fragments (B operand): column = this lane's row, k-slot = channels 16 s + 8 h
-    bf16x8 qf[NB][8];
-    long long out_row[NB];
-    bool row_ok[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int rr = row0 + wave * kRowsPerWave + nb * 32 + col;
-        row_ok[nb] = rr < rows_b;
-        const int sample = s0 + (row_ok[nb] ? rr : 0) / p.G;
-        const int head = j * p.G + (row_ok[nb] ? rr : 0) % p.G;
-        out_row[nb] = (long long)sample * p.Hq + head;
-        const uint4* qg = (const uint4*)p.q + out_row[nb] * kRowU4;
+    bf16x8 qf[8];
+    const int rr = row0 + wave * 32 + col;
+    const bool row_ok = rr < rows_b;
+    const long long out_row = (long long)(s0 + (row_ok ? rr : 0) / p.G) * p.Hq + j * p.G + (row_ok ? rr : 0) % p.G;
+    {
+        const uint4* qg = (const uint4*)p.q + out_row * kRowU4;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             uint4 v = qg[2 * s + h];
-            if (!row_ok[nb])
+            if (!row_ok)
                 v = make_uint4(0, 0, 0, 0);
-            qf[nb][s] = as_bf16x8(v);
+            qf[s] = as_bf16x8(v);
         }
     }
 
-    // ---- cooperative tile loads ---------------------------------------------------------------
-    // task 0..127: K rows 8 (task/16) .. + 7, piece task % 16
-    // task 128..255: V fragment (task-128)/16, piece (task-128) % 16
-    // The 8 loads of a task are issued two tiles ahead of their use and parked in registers.
-    uint4 stage[kTasks][8];
+    // ---- global -> LDS copies -------------------------------------------------------------------
+    // A tile takes 32 copy instructions (16 for K, 16 for V), each covering 4 token rows; wave w
+    // issues instructions w kIPW .. w kIPW + kIPW - 1.  Lane (r, c) of instruction q fetches piece
+    // c ^ swz(row) of row 4 (q & 15) + r.  Rows past the end of the split are clamped to its last
+    // token (their scores are masked later).  The four rows of an instruction lie in one page, so
+    // the page number is uniform over the wavefront.
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds;
+    const int lane_row = lane >> 4;
+    unsigned lane_off[kIPW];  // byte offset of this lane's piece for a full tile, relative to the group's first row
 #pragma unroll
-    for (int k = 0; k < kTasks; ++k)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            stage[k][e] = make_uint4(0, 0, 0, 0);
-    auto issue_loads = [&](int tb) __attribute__((always_inline)) {
-#pragma unroll
-        for (int k = 0; k < kTasks; ++k) {
-            const int task = kDeep ? (tid & 255) : tid + k * kThreads;
-            if (task < 256) {
-                const int piece = task & 15;
-                const int grp = (task >> 4) & 7;
-                const bool is_v = task >= 128;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int tl = is_v ? frag_token(grp, e) : 8 * grp + e;
-                    const int t = min(tb + tl, t1 - 1);
-                    const long long idx = row_index(t, piece);
-                    stage[k][e] = is_v ? vg[idx] : kg[idx];
-                }
-            }
-        }
-    };
-    auto store_tile = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int k = 0; k < kTasks; ++k) {
-            const int task = kDeep ? (tid & 255) : tid + k * kThreads;
-            const int piece = task & 15;
-            const int grp = (task >> 4) & 7;
-            if (task < 128) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    ksm[buf][8 * grp + e][piece] = stage[k][e];
-            } else if (task < 256) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-                    uint4 f;
-                    f.x = __builtin_amdgcn_perm(dword(stage[k][1], i >> 1), dword(stage[k][0], i >> 1), sel);
-                    f.y = __builtin_amdgcn_perm(dword(stage[k][3], i >> 1), dword(stage[k][2], i >> 1), sel);
-                    f.z = __builtin_amdgcn_perm(dword(stage[k][5], i >> 1), dword(stage[k][4], i >> 1), sel);
-                    f.w = __builtin_amdgcn_perm(dword(stage[k][7], i >> 1), dword(stage[k][6], i >> 1), sel);
-                    // channel 8 piece + i; fragment slot swizzled by the channel group
-                    vsm[buf][8 * piece + i][grp ^ (piece & 7)] = f;
-                }
-            }
-        }
-    };
-    float m_run[NB], l_run[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        m_run[nb] = -INFINITY;
-        l_run[nb] = 0.f;
+    for (int i = 0; i < kIPW; ++i) {
+        const int tl = 4 * ((wave * kIPW + i) & 15) + lane_row;
+        lane_off[i] = (unsigned)(lane_row * (unsigned)tok_stride + (((lane & 15) ^ swz(tl)) << 4));
     }
-    floatx16 o[4][NB];
+    // page numbers of the next tile to be copied, fetched one tile ahead of their use
+    int next_page[kIPW];
+    auto fetch_pages = [&](int tile) __attribute__((always_inline)) {
+        if (PAGED) {
+#pragma unroll
+            for (int i = 0; i < kIPW; ++i) {
+                const int tg = min(t0 + tile * kTileN + 4 * ((wave * kIPW + i) & 15), t1 - 1);
+                next_page[i] = pages[tg >> 4];
+            }
+        }
+    };
+    fetch_pages(0);
+    auto issue_tile = [&](int tile) __attribute__((always_inline)) {
+        const int tb = t0 + tile * kTileN;
+        const int stage = tile % kStages;
+        const bool full = tb + kTileN <= t1;
+#pragma unroll
+        for (int i = 0; i < kIPW; ++i) {
+            const int q = wave * kIPW + i;
+            const int g = 4 * (q & 15);  // first row of the group within the tile
+            const int tg = min(tb + g, t1 - 1);
+            long long base;              // uniform: byte offset of row tg
+            if (PAGED)
+                base = (long long)next_page[i] * page_stride + head_base + (tg & 15) * 256;
+            else
+                base = head_base + (long long)tg * tok_stride;
+            unsigned off = lane_off[i];
+            if (!full) {
+                const int rr = min(tg + lane_row, t1 - 1) - tg;  // clamped row within the group
+                off = (unsigned)(rr * (unsigned)tok_stride + (((lane & 15) ^ swz(g + lane_row)) << 4));
+            }
+            const char* src = (q < 16 ? kg : vg) + base + off;
+            uint4* dst = lds + (stage * kStageBytes + (q >> 4) * kTileBytes + (q & 15) * 1024) / 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        }
+        fetch_pages(tile + 1);
+    };
+
+    // ---- per-lane LDS addresses of the MFMA operand fragments (relative to a tile) ---------------
+    // K fragment (st, mb): row tl = 32 mb + col, piece (2 st + h) ^ swz(tl).  2 st has no bit 0 and
+    // h is bit 0 only, so the piece is 2 st ^ (h ^ swz(tl)) and its byte offset 32 st ^ k_xor[mb].
+    unsigned k_row[2], k_xor[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        const int tl = 32 * mb + col;
+        k_row[mb] = (unsigned)(tl * 256);
+        k_xor[mb] = (unsigned)((h ^ swz(tl)) << 4);
+    }
+    // V fragment (ks, db), half `part`: source lane (r, q4) of a 16-lane group points at token
+    // 16 ks + 8 part + 4 h + r, channels 32 db + 16 g16 + 4 q4 .. + 3; the transposing read then
+    // hands lane i of the group the four tokens of channel 32 db + 16 g16 + i.  The token step
+    // 16 ks only adds 4096 ks bytes (swz is periodic in 16) and goes into the offset field.
+    unsigned v_off[4][2];
+    {
+        const int g16 = (lane >> 4) & 1, r = (lane & 15) >> 2, q4 = lane & 3;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int part = 0; part < 2; ++part) {
+                const int tok = 8 * part + 4 * h + r;
+                const int piece = 4 * db + 2 * g16 + (q4 >> 1);
+                v_off[db][part] = (unsigned)(kTileBytes + tok * 256 + ((piece ^ swz(tok)) << 4) + (q4 & 1) * 8);
+            }
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;
+    floatx16 o[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                o[db][nb][i] = 0.f;
-    floatx16 sacc[2][NB];
-    bf16x8 pf[NB][4];  // P of the previous tile, B-operand layout
+        for (int i = 0; i < 16; ++i)
+            o[db][i] = 0.f;
+    floatx16 sacc[2];
+    bf16x8 pf[4];  // P of the previous tile, B-operand layout
 
-    // One MFMA region: the scores of tile `kbuf` (S^T = K Q^T, 16 MFMAs per column block) and,
-    // interleaved with them, O^T += V^T P^T for the previous tile `vbuf` (16 more).  The two
-    // products are independent, so their accumulator chains hide each other's latency; the
-    // scheduler is asked for a fragment pipeline (a few LDS reads up front, then one read per
-    // MFMA) so that no MFMA waits for the read issued right before it.
-    auto mfma_region = [&](auto do_qk, auto do_pv, int kbuf, int vbuf) __attribute__((always_inline)) {
-        constexpr bool QK = decltype(do_qk)::value, PV = decltype(do_pv)::value;
+    // One MFMA region: the scores of the tile in stage `ks` (16 MFMAs) and, alternating with
+    // them, O^T += V^T P^T for the previous tile in stage `vs` (16 more).  The two products are
+    // independent, so their accumulator chains hide each other's latency.  Fragments are read
+    // kAhead ahead of their MFMA.
+    // Ring of fragment registers: kAhead + 1 reads in flight, and one more slot so that a new
+    // read never targets the registers of the MFMA issued just before it.
+    u32x4 ring[kAhead + 2];
+    auto region = [&](auto qk_tag, auto pv_tag, int kstage, int vstage) __attribute__((always_inline)) {
+        constexpr bool QK = decltype(qk_tag)::value, PV = decltype(pv_tag)::value;
+        constexpr int NF = frag_count<QK, PV>();
+        const unsigned kbase = lds_base + kstage * kStageBytes;
+        const unsigned vbase = lds_base + vstage * kStageBytes;
         if (QK) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        sacc[mb][nb][i] = 0.f;
+                for (int i = 0; i < 16; ++i)
+                    sacc[mb][i] = 0.f;
         }
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            if (QK) {
-                const int st = k >> 1, mb = k & 1;
-                const bf16x8 kf = as_bf16x8(ksm[kbuf][32 * mb + col][2 * st + h]);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    sacc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][st], sacc[mb][nb], 0, 0, 0);
+        auto issue = [&](auto kc) __attribute__((always_inline)) {
+            constexpr int K = decltype(kc)::value;
+            if constexpr (K < NF) {
+                using F = Frag<QK, PV, K>;
+                u32x4& dst = ring[K % (kAhead + 2)];
+                if constexpr (!F::is_pv) {
+                    const unsigned addr = kbase + k_row[F::b] + ((32u * F::a) ^ k_xor[F::b]);
+                    asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
+                } else {
+                    u32x2 lo, hi;
+                    const unsigned a0 = vbase + v_off[F::b][0], a1 = vbase + v_off[F::b][1];
+                    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%4\n\tds_read_b64_tr_b16 %1, %3 offset:%4"
+                                 : "=&v"(lo), "=&v"(hi)
+                                 : "v"(a0), "v"(a1), "n"(F::a * 4096));
+                    dst = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
             }
-            if (PV) {
-                const int ks = k >> 2, db = k & 3;
-                const int ch = 32 * db + col;
-                const bf16x8 vf = as_bf16x8(vsm[vbuf][ch][(2 * ks + h) ^ ((ch >> 3) & 7)]);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    o[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][ks], o[db][nb], 0, 0, 0);
-            }
-        }
-        constexpr int kFrags = (QK ? 16 : 0) + (PV ? 16 : 0);
-        constexpr int kAhead = 6;
-        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-        for (int k = 0; k < kFrags - kAhead; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kAhead * NB, 0);
+        };
+        auto consume = [&](auto kc) __attribute__((always_inline)) {
+            constexpr int K = decltype(kc)::value;
+            using F = Frag<QK, PV, K>;
+            u32x4& f = ring[K % (kAhead + 2)];
+            asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(ops_after<QK, PV, K>()));
+            if constexpr (!F::is_pv)
+                sacc[F::b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f), qf[F::a], sacc[F::b], 0, 0, 0);
+            else
+                o[F::b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f), pf[F::a], o[F::b], 0, 0, 0);
+        };
+        for_each_index(issue, std::make_integer_sequence<int, kAhead + 1>{});
+        for_each_index(
+            [&](auto kc) __attribute__((always_inline)) {
+                consume(kc);
+                issue(std::integral_constant<int, decltype(kc)::value + kAhead + 1>{});
+            },
+            std::make_integer_sequence<int, NF>{});
     };
 
     // Online softmax of the scores in `sacc` (lane-local per row): updates (m, l), rescales O
@@ -242,123 +298,123 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     // the accumulator; the scale is folded into the exponent: p = 2^(s * scale - m).
     auto softmax_tile = [&](int tb) __attribute__((always_inline)) {
         const bool full = tb + kTileN <= t1;  // only the last tile of a split can be ragged
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if (!full) {
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        // accumulator register i of lane-half h is token 32 mb + 8 (i/4) + 4 h + i%4
-                        const int t = tb + 32 * mb + 8 * (i >> 2) + 4 * h + (i & 3);
-                        if (t >= t1)
-                            sacc[mb][nb][i] = -INFINITY;
-                    }
-            }
-            float tmax = -INFINITY;
+        if (!full) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    // accumulator register i of lane-half h is token 32 mb + 8 (i/4) + 4 h + i%4
+                    const int t = tb + 32 * mb + 8 * (i >> 2) + 4 * h + (i & 3);
+                    if (t >= t1)
+                        sacc[mb][i] = -INFINITY;
+                }
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                tmax = fmaxf(tmax, sacc[mb][i]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * p.scale_log2;
+        // The reference maximum m only has to bound the exponents, so it is raised only when some
+        // row of this wavefront exceeds it by more than kSlack (p <= 2^kSlack otherwise, exact in
+        // fp32 and bf16 alike); the accumulators then need no rescale on most tiles.
+        constexpr float kSlack = 8.f;
+        const bool raise = __ballot(tmax > m_run + kSlack) != 0;
+        float corr = 1.f;
+        if (raise) {
+            const float m_up = fmaxf(m_run, tmax);
+            corr = __builtin_amdgcn_exp2f(m_run - m_up);
+            m_run = m_up;
+        }
+        const float m_new = m_run;
+        float psum = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                float pv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[mb][8 * u + e], p.scale_log2, -m_new));
+                    psum += pv[e];
+                }
+                uint4 pu;
+                pu.x = pack_bf16_rne(pv[0], pv[1]);
+                pu.y = pack_bf16_rne(pv[2], pv[3]);
+                pu.z = pack_bf16_rne(pv[4], pv[5]);
+                pu.w = pack_bf16_rne(pv[6], pv[7]);
+                pf[2 * mb + u] = as_bf16x8(pu);
+            }
+        l_run = l_run * corr + psum;
+        if (raise) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    tmax = fmaxf(tmax, sacc[mb][nb][i]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float m_new = fmaxf(m_run[nb], tmax * p.scale_log2);
-            const float corr = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-            m_run[nb] = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    float pv[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[mb][nb][8 * u + e], p.scale_log2, -m_new));
-                        psum += pv[e];
-                    }
-                    uint4 pu;
-                    pu.x = pack_bf16_rne(pv[0], pv[1]);
-                    pu.y = pack_bf16_rne(pv[2], pv[3]);
-                    pu.z = pack_bf16_rne(pv[4], pv[5]);
-                    pu.w = pack_bf16_rne(pv[6], pv[7]);
-                    pf[nb][2 * mb + u] = as_bf16x8(pu);
-                }
-            l_run[nb] = l_run[nb] * corr + psum;
-            if (__ballot(corr != 1.f)) {
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        o[db][nb][i] *= corr;
-            }
+                    o[db][i] *= corr;
         }
     };
 
-    // Pipeline over tiles (three LDS buffers).  Iteration `it` issues the global loads of tile
-    // it+1, runs one MFMA region (scores of tile `it` together with P V of tile it-1), then the
-    // softmax of tile `it` on the vector ALU (which the other wavefront of the SIMD overlaps
-    // with its own MFMA region), and parks tile it+1 in LDS.  One barrier per tile.
+    // ---- pipeline over tiles ----------------------------------------------------------------------
+    // Iteration `it` starts the copies of tile it+2, runs one MFMA region (scores of tile `it`
+    // together with P V of tile it-1), waits until its own copies of tile it+1 have landed, meets
+    // the other wavefronts at a barrier, then runs the softmax of tile `it`.
     const int ntiles = (t1 - t0 + kTileN - 1) / kTileN;
     const std::true_type yes{};
     const std::false_type no{};
-    const int half = kDeep ? (tid >> 8) : 0;  // which tiles this thread carries (deep mode)
-    auto mine = [&](int tile) { return !kDeep || (tile & 1) == half; };
-    if (mine(0))
-        issue_loads(t0);
-    if (kDeep && mine(1) && ntiles > 1)
-        issue_loads(t0 + kTileN);
-    if (mine(0))
-        store_tile(0);
-    if (!kDeep && ntiles > 1)
-        issue_loads(t0 + kTileN);
-    if (kDeep && mine(2) && ntiles > 2)
-        issue_loads(t0 + 2 * kTileN);
-    __syncthreads();
-    mfma_region(yes, no, 0, 0);
-    softmax_tile(t0);
-    if (ntiles > 1) {
-        if (mine(1))
-            store_tile(1);
-        __syncthreads();
-    }
-    for (int it = 1; it < ntiles; ++it) {
-        const int tb = t0 + it * kTileN;
-        if (kDeep) {
-            if (mine(it + 2) && it + 2 < ntiles)
-                issue_loads(tb + 2 * kTileN);
-        } else if (it + 1 < ntiles) {
-            issue_loads(tb + kTileN);
-        }
-        mfma_region(yes, yes, it % 3, (it - 1) % 3);
-        softmax_tile(tb);
+    issue_tile(0);
+    if (ntiles > 1)
+        issue_tile(1);
+    if (ntiles > 1)
+        wait_vmcnt<kIPW>();
+    else
+        wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    // One barrier per tile, after the MFMA region (own copies of the next tile have landed by
+    // then).  A copy into a ring slot is issued only after a barrier that every wavefront reaches
+    // after its last read of that slot, and a tile is read only after a barrier that every
+    // wavefront reaches after its copies of that tile landed.
+    auto end_of_region = [&](int it) __attribute__((always_inline)) {
         if (it + 1 < ntiles) {
-            if (mine(it + 1))
-                store_tile((it + 1) % 3);
-            __syncthreads();
+            if (it + 2 < ntiles)
+                wait_vmcnt<kIPW>();
+            else
+                wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
         }
+    };
+    // first tile: scores only (kept out of the loop so that the loop body is one straight path)
+    if (ntiles > 2)
+        issue_tile(2);
+    region(yes, no, 0, 0);
+    end_of_region(0);
+    softmax_tile(t0);
+    for (int it = 1; it < ntiles; ++it) {
+        if (it + 2 < ntiles)
+            issue_tile(it + 2);
+        region(yes, yes, it % kStages, (it - 1) % kStages);
+        end_of_region(it);
+        softmax_tile(t0 + it * kTileN);
     }
-    mfma_region(no, yes, 0, (ntiles - 1) % 3);
+    region(no, yes, 0, (ntiles - 1) % kStages);
 
     // ---- write the partial state ------------------------------------------------------------------
+    const float l = l_run + __shfl_xor(l_run, 32);
+    if (!row_ok)
+        return;
+    const long long prow = part_index(p, out_row, split);
+    if (h == 0)
+        p.part_ml[prow] = make_float2(m_run, l);
+    float* dst = p.part_acc + prow * kD;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const float l = l_run[nb] + __shfl_xor(l_run[nb], 32);
-        if (!row_ok[nb])
-            continue;
-        const long long prow = part_index(p, out_row[nb], split);
-        if (h == 0)
-            p.part_ml[prow] = make_float2(m_run[nb], l);
-        float* dst = p.part_acc + prow * kD;
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                // registers 4 q4 .. 4 q4 + 3 are channels 32 db + 8 q4 + 4 h .. + 3
-                float4 v = make_float4(o[db][nb][4 * q4], o[db][nb][4 * q4 + 1], o[db][nb][4 * q4 + 2],
-                                       o[db][nb][4 * q4 + 3]);
-                *reinterpret_cast<float4*>(dst + 32 * db + 8 * q4 + 4 * h) = v;
-            }
-    }
+        for (int q4 = 0; q4 < 4; ++q4) {
+            // registers 4 q4 .. 4 q4 + 3 are channels 32 db + 8 q4 + 4 h .. + 3
+            float4 v = make_float4(o[db][4 * q4], o[db][4 * q4 + 1], o[db][4 * q4 + 2], o[db][4 * q4 + 3]);
+            *reinterpret_cast<float4*>(dst + 32 * db + 8 * q4 + 4 * h) = v;
+        }
 }
 
 template <int WAVES>
@@ -368,9 +424,9 @@ hipError_t launch_waves(const AttnParams& p, hipStream_t s)
     const int rowtiles = (p.max_spp * p.G + kBlockRows - 1) / kBlockRows;
     const dim3 grid(p.num_prefix_splits, rowtiles, p.B * p.Hkv);
     if (p.page_size)
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, 1, true>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, true>), grid, dim3(WAVES * 64), 0, s, p);
     else
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, 1, false>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, false>), grid, dim3(WAVES * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -379,7 +435,7 @@ hipError_t launch_waves(const AttnParams& p, hipStream_t s)
 bool prefix_mfma_supported(const AttnParams& p)
 {
     return p.dtype == 1 && p.D == kD && p.prefix_split_tokens % kTileN == 0 &&
-           (long long)p.B * p.Hkv <= 65535;
+           (p.page_size == 0 || p.page_size == 16) && (long long)p.B * p.Hkv <= 65535;
 }
 
 // Rows per workgroup used for a problem with `rows` query rows per (prompt, KV head):
