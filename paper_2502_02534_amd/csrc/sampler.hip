@@ -1,6 +1,6 @@
 // Temperature / nucleus / inverse-CDF token sampler.
 //
-// Two paths.  The sliced path (below, four stream-ordered kernels) reads a row from HBM once,
+// Two paths.  The sliced path (below, two stream-ordered kernels) reads a row from HBM once,
 // takes a second look that caches serve when the logits fit, and finds the exact nucleus
 // threshold without sorting.  The whole-row routine (one workgroup per row, every pass from
 // memory) covers rows the sliced path does not take: unaligned rows, vocabularies beyond
@@ -403,23 +403,27 @@ __device__ void sample_row_from_memory(const SamplerParams& sp, long long r, Row
 
 // =============================================================================================
 // Sliced path: a row is cut into `slices` contiguous pieces of at most kSliceMax elements and
-// handled by four small kernels in stream order (no workgroup ever waits for another):
+// handled by two kernels in stream order (no workgroup ever waits for another):
 //
-//   hist   (rows x slices)  one HBM pass: slice maximum (and its lowest index) and a histogram
-//          of scaled mass over bins of width 1/16 in log2 p.  The bin of a logit is
-//          floor(x c 16), an integer function of x alone; a histogram built against the slice
-//          maximum differs from one built against the row maximum by an integer shift.
-//          Mass is accumulated in u32 fixed point relative to the bin's own reference
-//          (q = 2^(frac/16) 2^15 in [32768, 34219]), which needs no maximum at all.
-//   cut    (rows)           combines the slices' histograms and picks the bin that holds the
-//          nucleus cut, plus a neighbour when the estimate cannot decide.
-//   mass   (rows x slices)  second look at the slice (served by cache when the logits fit):
-//          p_i = 2^((x_i - row max) c) exactly as defined, slice mass in fp64, mass of the
-//          certainly-kept elements per 256-element segment in vocabulary order, and the
-//          elements of the cut bins as candidates (logit, index).
-//   pick   (rows)           exact threshold among the candidates by radix select on the logit's
-//          bit pattern with fp64 masses, kept candidates added to their segments, scan of the
-//          segments, walk inside the segment that contains u * Z.
+//   hist    (rows x slices)  one HBM pass: slice maximum (and its lowest index) and a histogram
+//           of scaled mass over bins of width 1/16 in log2 p.  The bin of a logit is
+//           floor(x c 16), an integer function of x alone; a histogram built against the slice
+//           maximum differs from one built against the row maximum by an integer shift.
+//           Mass is accumulated in u32 fixed point relative to the bin's own reference
+//           (q = 2^(frac/16) 2^15 in [32768, 34219]), which needs no maximum at all.
+//   select  (rows x slices)  second look at the slice (served by cache when the logits fit).
+//           Every workgroup first combines the row's slice histograms and picks the bin that
+//           holds the nucleus cut, plus a neighbour when the estimate cannot decide (the same
+//           arithmetic in every workgroup of a row, so they agree).  Then, with
+//           p_i = 2^((x_i - row max) c) exactly as defined: slice mass in fp64, mass of the
+//           certainly-kept elements per 256-element segment in vocabulary order, and the
+//           elements of the cut bins as candidates (logit, index).  The workgroup of a row that
+//           finishes last finds the exact threshold among the candidates by radix select on the
+//           logit's bit pattern with fp64 masses, adds the kept candidates to their segments,
+//           scans the segments and walks inside the segment that contains u * Z.
+//
+// What the workgroups of a row hand to the last one goes through memory with agent-scope
+// accesses (written through, read past the local L2), ordered by an arrival counter.
 // =============================================================================================
 constexpr int kIter = kBlock * 4;         // elements one float4 per thread covers
 constexpr int kSliceMax = 8 * kIter;      // elements per workgroup: 8 float4 per thread
@@ -432,30 +436,27 @@ static_assert(kMaxSlices * kSegPerSlice <= kMaxSegments, "segment table too smal
 struct SliceStat {
     float max_x;
     int argmax;
-    float kf_max;   // floor(max_x * c16)
-    int nbins;      // histogram bins written
-    double mass;    // sum of p over the slice (mass kernel)
-    double above;   // mass of certainly-kept elements (mass kernel)
+    double mass;    // sum of p over the slice (select kernel)
+    double above;   // mass of certainly-kept elements (select kernel)
 };
 
-struct RowCut {
-    float max_x;        // row maximum
-    float kf_row;       // floor(max_x * c16)
-    int lo, hi;         // candidate bins, counted down from the maximum's bin; kBins = no cut
-    int done;           // 1 = token already written (greedy row)
-    unsigned cand_total;
+// Counters of a row, zeroed by the hist kernel for the select kernel that follows it.
+struct RowCtl {
+    unsigned arrived;     // workgroups of the row that have published their results
+    unsigned cand_total;  // candidates appended so far
+    int lo, hi;           // cut bins, when the per-row cut kernel ran
 };
 
 __host__ __device__ inline size_t sliced_row_bytes(int slices)
 {
-    return 256 + (size_t)slices * 64 + (size_t)slices * kBins * 4 + (size_t)slices * kSegPerSlice * 8 +
+    return 256 + (size_t)slices * 64 + (size_t)slices * kPubBins * 4 + (size_t)slices * kSegPerSlice * 8 +
            (size_t)kCandCap * 8;
 }
 
 struct RowWs {
-    RowCut* cut;
+    RowCtl* ctl;
     SliceStat* stat;      // [slices], 64 B apart
-    unsigned* hist;       // [slices][kBins]
+    unsigned* hist;       // [slices][kPubBins]
     double* seg;          // [slices][kSegPerSlice]
     unsigned long long* cand;  // [kCandCap] logit bits | index << 32
 };
@@ -464,12 +465,12 @@ __device__ __forceinline__ RowWs row_ws(char* base, long long row, int slices)
 {
     char* p = base + row * sliced_row_bytes(slices);
     RowWs w;
-    w.cut = (RowCut*)p;
+    w.ctl = (RowCtl*)p;
     p += 256;
     w.stat = (SliceStat*)p;
     p += (size_t)slices * 64;
     w.hist = (unsigned*)p;
-    p += (size_t)slices * kBins * 4;
+    p += (size_t)slices * kPubBins * 4;
     w.seg = (double*)p;
     p += (size_t)slices * kSegPerSlice * 8;
     w.cand = (unsigned long long*)p;
@@ -479,6 +480,16 @@ __device__ __forceinline__ RowWs row_ws(char* base, long long row, int slices)
 __device__ __forceinline__ SliceStat* stat_at(const RowWs& w, int s)
 {
     return (SliceStat*)((char*)w.stat + (size_t)s * 64);
+}
+
+// Agent-scope accesses for data that one workgroup writes and another reads inside one kernel.
+template <typename T> __device__ __forceinline__ void publish(T* p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ T observe(const T* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Monotone map of a float onto unsigned integers (larger float -> larger key).
@@ -529,24 +540,34 @@ __device__ __forceinline__ SliceRange slice_range(int slice, int slice_elems, in
     return g;
 }
 
+// Every load is unconditional (lanes past the end re-read the slice's last float4), so that the
+// hardware's in-order load counter stays exact for the compiler and later loads need not wait
+// for these.  SPD_MASK_SLICE, applied where the values are first needed, replaces what lies
+// past the end by -inf.  Every slice holds at least one whole float4 (the host sends rows
+// shorter than that to the whole-row kernel, and slices are never shorter than about 2000).
 #define SPD_LOAD_SLICE(xv, x, g, tid)                                                   \
     _Pragma("unroll") for (int j = 0; j < 8; ++j)                                       \
     {                                                                                   \
         const int i_ = (g).e0 + j * kIter + (tid) * 4;                                  \
-        float4 v_ = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);            \
-        if (i_ < (g).v4end)                                                             \
-            v_ = *reinterpret_cast<const float4*>((x) + i_);                            \
+        const float4 v_ = *reinterpret_cast<const float4*>((x) + min(i_, (g).v4end - 4)); \
         (xv)[4 * j] = v_.x;                                                             \
         (xv)[4 * j + 1] = v_.y;                                                         \
         (xv)[4 * j + 2] = v_.z;                                                         \
         (xv)[4 * j + 3] = v_.w;                                                         \
+    }
+#define SPD_MASK_SLICE(xv, g, tid)                                                      \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                       \
+    {                                                                                   \
+        if (!((g).e0 + j * kIter + (tid) * 4 < (g).v4end)) {                            \
+            (xv)[4 * j] = (xv)[4 * j + 1] = (xv)[4 * j + 2] = (xv)[4 * j + 3] = -INFINITY; \
+        }                                                                               \
     }
 
 // ---- kernel 1: slice maximum and histogram -----------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, char* ws, int slices,
                                                               int slice_elems)
 {
-    __shared__ unsigned hist[kBins];
+    __shared__ unsigned hist[kPubBins];
     __shared__ float red_f[kWaves];
     __shared__ int red_i[kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -561,6 +582,11 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
 
     float xv[32];
     SPD_LOAD_SLICE(xv, x, g, tid)
+    SPD_MASK_SLICE(xv, g, tid)
+    if (slice == 0 && tid == 0) {
+        W.ctl->arrived = 0u;
+        W.ctl->cand_total = 0u;
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int q = 0; q < 32; ++q)
@@ -572,7 +598,7 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
         mx = fmaxf(mx, __shfl_xor(mx, o));
     if (lane == 0)
         red_f[wave] = mx;
-    for (int b = tid; b < kBins; b += kBlock)
+    for (int b = tid; b < kPubBins; b += kBlock)
         hist[b] = 0u;
     __syncthreads();
     mx = red_f[0];
@@ -598,11 +624,9 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
             mi = min(mi, red_i[w]);
     }
 
-    const RowConst rc = row_const(greedy ? 1.f : T);
-    const float kf_loc = bin_coord(mx, rc.c16);
-    int nbins = 0;
     if (cut) {
-        int bmax = -1;
+        const RowConst rc = row_const(T);
+        const float kf_loc = bin_coord(mx, rc.c16);
         auto add = [&](float xq) {
             const float t = xq * rc.c16;
             const float kf = floorf(t);
@@ -610,7 +634,6 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
             // mass relative to the bin's own reference 2^(kf/16): 2^(frac/16) in [1, 2^(1/16))
             const unsigned q = (unsigned)(__builtin_amdgcn_exp2f((t - kf) * 0.0625f) * 32768.f + 0.5f);
             atomicAdd(&hist[b], q);
-            bmax = max(bmax, b);
         };
 #pragma unroll
         for (int q = 0; q < 32; ++q)
@@ -619,347 +642,305 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
         if (tid == 0)
             for (int k = 0; k < g.ntail; ++k)
                 add(x[g.v4end + k]);
-        (void)bmax;
         __syncthreads();  // histogram complete
-        // a fixed number of bins is written so that the reader needs nothing else to fetch them
-        nbins = kPubBins;
         for (int b = tid; b < kPubBins; b += kBlock)
-            W.hist[(size_t)slice * kBins + b] = hist[b];
+            W.hist[(size_t)slice * kPubBins + b] = hist[b];
     }
     if (tid == 0) {
         SliceStat* st = stat_at(W, slice);
         st->max_x = mx;
         st->argmax = mi;
-        st->kf_max = kf_loc;
-        st->nbins = nbins;
     }
 }
 
-// 2^(-k/16), k = 0..15
-__device__ const double kRoot16[16] = {
-    1.0,                 0.95760328069857365, 0.91700404320467122, 0.87812608018664974,
-    0.84089641525371454, 0.80524516597462716, 0.77110541270397041, 0.73841307296974966,
-    0.70710678118654752, 0.67712777346844633, 0.64841977732550483, 0.62092890603674203,
-    0.59460355750136054, 0.56939431737834583, 0.54525386633262883, 0.52213689121370692};
+// ---- bin selection by one wavefront ----------------------------------------------------------------
+// A histogram of kBins doubles in "rank order" (bin 0 = most probable) is kept transposed in
+// LDS, bin b in slot (b & 31) * 64 + (b >> 5), so that lane l owns the 32 consecutive bins
+// 32 l .. 32 l + 31 and the 64 lanes read consecutive slots.
+__device__ __forceinline__ int rank_slot(int b) { return (b & 31) * 64 + (b >> 5); }
 
-// ---- kernel 2: the row's cut bins --------------------------------------------------------------------
-struct CutLds {
-    double hist[kBins];
-    double scratch[kWaves];
-    float smax[kMaxSlices];
-    int snb[kMaxSlices];
-    int sarg[kMaxSlices];
-    int shift[kMaxSlices];
-    int sh_bin, sh_low;
-    double sh_above;
+struct BinPick {
+    int bin;        // first non-empty bin whose cumulative mass reaches `need`
+    double above;   // mass strictly above it (including `above0`)
+    double in_bin;  // its own mass
+    double total;   // sum of the histogram
 };
 
+// Every lane of the calling wavefront returns the same result; no workgroup barrier is used, so
+// all wavefronts of a workgroup may call it redundantly on a finished histogram.  With
+// `relative`, `need` is a fraction of the histogram's total.  If rounding leaves even the total
+// short of `need`, the last non-empty bin is taken (everything is kept).
+__device__ __forceinline__ BinPick wave_pick(const double* H, double above0, double need, bool relative)
+{
+    const int lane = threadIdx.x & 63;
+    double own = 0.0;
+#pragma unroll 8
+    for (int k = 0; k < 32; ++k)
+        own += H[k * 64 + lane];
+    double incl = own;
+    for (int o = 1; o < 64; o <<= 1) {
+        const double up = __shfl_up(incl, o);
+        if (lane >= o)
+            incl += up;
+    }
+    BinPick r;
+    r.total = __shfl(incl, 63);
+    if (relative)
+        need *= r.total;
+    const double before_lane = above0 + (incl - own);
+    const unsigned long long nonempty = __ballot(own > 0.0);
+    const unsigned long long hit = __ballot(own > 0.0 && before_lane + own >= need);
+    r.bin = 0;
+    r.above = above0;
+    r.in_bin = 0.0;
+    if (!nonempty)
+        return r;
+    const int hl = hit ? __ffsll((long long)hit) - 1 : 63 - __clzll((long long)nonempty);
+    // the 32 bins of lane hl, one per lane (both halves of the wavefront hold the same), scanned
+    const double h = H[(lane & 31) * 64 + hl];
+    double cum = h;
+    for (int o = 1; o < 32; o <<= 1) {
+        const double up = __shfl_up(cum, o);
+        if ((lane & 31) >= o)
+            cum += up;
+    }
+    cum += __shfl(before_lane, hl);
+    const unsigned ne32 = (unsigned)__ballot(h > 0.0);
+    const unsigned hit32 = hit ? (unsigned)__ballot(h > 0.0 && cum >= need) : 0u;
+    // first bin that reaches `need`; else (rounding, or nothing reaches it) the last non-empty one
+    const int k = hit32 ? __ffs((int)hit32) - 1 : 31 - __clz((int)ne32);
+    r.bin = 32 * hl + k;
+    r.in_bin = __shfl(h, k);
+    r.above = __shfl(cum, k) - r.in_bin;
+    return r;
+}
+
+// Two block-wide fp64 sums at once (fixed reduction tree).
+__device__ void block_sum2_f64(double& a, double& b, double* scratch /* 2 kWaves */)
+{
+    a = wave_sum_f64(a);
+    b = wave_sum_f64(b);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        scratch[threadIdx.x >> 6] = a;
+        scratch[kWaves + (threadIdx.x >> 6)] = b;
+    }
+    __syncthreads();
+    a = 0.0;
+    b = 0.0;
+    for (int w = 0; w < kWaves; ++w) {
+        a += scratch[w];
+        b += scratch[kWaves + w];
+    }
+}
+
+// ---- kernel 2: cut bins, exact masses, candidates; last workgroup of a row: threshold and walk ----------
+struct SelectLds {
+    RowLds row;                           // hist / scratch / seg_mass of the row routines
+    unsigned long long cand[kCandCap];    // candidates of the row (last workgroup only)
+    double smass[kMaxSlices];
+    double sabove[kMaxSlices];
+    float smax[kMaxSlices];
+    int sarg[kMaxSlices];
+    int shift[kMaxSlices];
+    int wave_cnt[kWaves];
+    unsigned cand_base;
+    unsigned arrived_before;
+    uint32_t kmin[kWaves], kmax[kWaves];
+};
+
+// Estimate of the nucleus cut from the slices' histograms: the candidate bins [lo, hi] of the
+// row, counted down from the bin of the row maximum.  Called by a whole workgroup; L.smax
+// holds the slice maxima.  The arithmetic depends only on the row's data, so every workgroup
+// that evaluates it for a row gets the same bins.
+struct CutBins {
+    int lo, hi;
+};
+
+__device__ __forceinline__ CutBins estimate_cut(SelectLds& L, const RowWs& W, int slices, float kf_row, const RowConst& rc,
+                                float top_p)
+{
+    const int tid = threadIdx.x;
+    int lo, hi;
+    if (tid < slices)
+        L.shift[tid] = L.smax[tid] == -INFINITY
+                           ? kBins
+                           : (int)fminf(fmaxf(kf_row - bin_coord(L.smax[tid], rc.c16), 0.f), (float)kBins);
+    __syncthreads();
+    // Bin b of slice s is bin b + shift[s] of the row; its mass is q 2^-15 2^(-bin/16) relative
+    // to the reference of the row maximum's bin.  Thread t gathers row bins 4 t .. 4 t + 3
+    // (all loads of eight slices are requested before any is used).
+    const int rb0 = kBinsPerThread * tid;
+    unsigned long long qsum[kBinsPerThread];
+#pragma unroll
+    for (int k = 0; k < kBinsPerThread; ++k)
+        qsum[k] = 0ull;
+    for (int s0 = 0; s0 < slices; s0 += 8) {
+        // unconditional loads from clamped positions (a guarded load would be waited for on
+        // the spot); what lies outside a slice's published bins is masked afterwards
+        unsigned qv[8][kBinsPerThread];
+        int sh[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int sl = min(s0 + u, slices - 1);
+            sh[u] = s0 + u < slices ? L.shift[sl] : kBins;
+#pragma unroll
+            for (int k = 0; k < kBinsPerThread; ++k) {
+                const int b = min(max(rb0 + k - sh[u], 0), kPubBins - 1);
+                qv[u][k] = W.hist[(size_t)sl * kPubBins + b];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int k = 0; k < kBinsPerThread; ++k) {
+                const int b = rb0 + k - sh[u];
+                qsum[k] += (b >= 0 && b < kPubBins) ? qv[u][k] : 0u;
+            }
+    }
+#pragma unroll
+    for (int k = 0; k < kBinsPerThread; ++k) {
+        const int rb = rb0 + k;
+        // 2^(-(rb mod 16)/16) in fp32 (an estimate is all that is needed), 2^(-15 - rb/16) as
+        // an exponent
+        const double root = (double)__builtin_amdgcn_exp2f(-0.0625f * (float)(rb & 15));
+        const double pow2 = __hiloint2double((1023 - 15 - (rb >> 4)) << 20, 0);
+        L.row.hist[rank_slot(rb)] = (double)qsum[k] * root * pow2;
+    }
+    __syncthreads();
+    const BinPick est = wave_pick(L.row.hist, 0.0, (double)top_p, true);
+    // the estimate is good to about 1e-5 of the total; be generous
+    const double need_est = (double)top_p * est.total, tol = 1e-3 * est.total;
+    lo = hi = est.bin;
+    if (need_est - est.above <= tol && lo > 0)
+        --lo;
+    if (est.above + est.in_bin - need_est <= tol && hi < kBins - 1)
+        ++hi;
+    __syncthreads();  // the histogram array is reused below
+    CutBins c;
+    c.lo = lo;
+    c.hi = hi;
+    return c;
+}
+
+// ---- optional kernel between the two: the row's cut bins, once per row ------------------------------
+// Used when a launch has so many workgroups that recomputing the estimate in each of them
+// would cost more than one more small kernel.
 __global__ __launch_bounds__(kBlock) void sampler_cut_kernel(SamplerParams sp, char* ws, int slices)
 {
-    __shared__ CutLds L;
+    __shared__ SelectLds L;
     const int tid = threadIdx.x;
     const long long r = blockIdx.x;
     const RowWs W = row_ws(ws, r, slices);
     const float T = sp.temperature[r];
-    const bool greedy = (T == 0.f);
     const float top_p = sp.top_p[r];
-    const bool cut = !greedy && top_p < 1.f;
-    // everything this kernel reads from memory is requested up front, in one round
-    constexpr int kPerThread = kMaxSlices * kPubBins / kBlock;
-    unsigned qv[kPerThread];
-#pragma unroll
-    for (int u = 0; u < kPerThread; ++u) {
-        const int it = tid + u * kBlock;
-        const int sl = it / kPubBins, b = it % kPubBins;
-        qv[u] = (cut && sl < slices) ? W.hist[(size_t)sl * kBins + b] : 0u;
-    }
-    if (tid < slices) {
-        const SliceStat* st = stat_at(W, tid);
-        L.smax[tid] = st->max_x;
-        L.snb[tid] = st->nbins;
-        L.sarg[tid] = st->argmax;
-    }
+    if (T == 0.f || !(top_p < 1.f))
+        return;
+    if (tid < slices)
+        L.smax[tid] = stat_at(W, tid)->max_x;
     __syncthreads();
     float M = -INFINITY;
-    int nb_max = 0, arg = 0x7fffffff;
-    for (int s = 0; s < slices; ++s) {
-        if (L.smax[s] > M || (L.smax[s] == M && L.sarg[s] < arg)) {
-            M = L.smax[s];
-            arg = L.sarg[s];
-        }
-        nb_max = max(nb_max, L.snb[s]);
-    }
-    const RowConst rc = row_const(greedy ? 1.f : T);
-    const float kf_row = bin_coord(M, rc.c16);
-    int lo = kBins, hi = kBins;
-    if (cut) {
-        if (tid < slices)
-            L.shift[tid] = L.smax[tid] == -INFINITY
-                               ? 0
-                               : (int)fminf(fmaxf(kf_row - bin_coord(L.smax[tid], rc.c16), 0.f), (float)kBins);
-        for (int b = tid; b < kBins; b += kBlock)
-            L.hist[b] = 0.0;
-        __syncthreads();
-        // bin b of slice s is bin b + shift[s] of the row; mass = q 2^-15 2^(-bin/16) relative to
-        // the reference of the row maximum's bin.  Stored mirrored (most probable bin last) for
-        // pick_bin.
-#pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            if (qv[u]) {
-                const int it = tid + u * kBlock;
-                const int sl = it / kPubBins, b = it % kPubBins;
-                const int rb = min(b + L.shift[sl], kBins - 1);
-                // q 2^-15 2^(-rb/16): sixteenth roots from a table, the rest is an exponent shift
-                atomicAdd(&L.hist[kBins - 1 - rb], ldexp((double)qv[u] * kRoot16[rb & 15], -15 - (rb >> 4)));
-            }
-        }
-        __syncthreads();
-        double part = 0.0;
-        for (int b = tid; b < kBins; b += kBlock)
-            part += L.hist[b];
-        const double S_est = block_sum_f64(part, L.scratch);
-        const double need = (double)top_p * S_est;
-        pick_bin(L.hist, 0.0, need, &L.sh_bin, &L.sh_low, &L.sh_above, L.scratch);
-        const int bsel = kBins - 1 - L.sh_bin;
-        const double above_est = L.sh_above, in_bin = L.hist[L.sh_bin];
-        // the estimate is good to about 1e-5 of the total; be generous
-        const double tol = 1e-3 * S_est;
-        lo = hi = bsel;
-        if (need - above_est <= tol && lo > 0)
-            --lo;
-        if (above_est + in_bin - need <= tol && hi < kBins - 1)
-            ++hi;
-    }
+    for (int s = 0; s < slices; ++s)
+        M = fmaxf(M, L.smax[s]);
+    const RowConst rc = row_const(T);
+    const CutBins cb = estimate_cut(L, W, slices, bin_coord(M, rc.c16), rc, top_p);
     if (tid == 0) {
-        RowCut* c = W.cut;
-        c->max_x = M;
-        c->kf_row = kf_row;
-        c->lo = lo;
-        c->hi = hi;
-        c->done = greedy ? 1 : 0;
-        c->cand_total = 0u;
-        if (greedy)
-            sp.tokens[r] = arg == 0x7fffffff ? 0 : arg;
+        W.ctl->lo = cb.lo;
+        W.ctl->hi = cb.hi;
     }
 }
 
-// ---- kernel 3: exact masses, segments, candidates -------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void sampler_mass_kernel(SamplerParams sp, char* ws, int slices,
-                                                              int slice_elems)
+// ---- exact threshold among the candidates, CDF walk: one workgroup per row -----------------------------
+// Runs in the workgroup of a row that finished last (select kernel) or in a kernel of its own.
+__device__ __forceinline__ void finish_row(SelectLds& L, const SamplerParams& sp, long long r, const RowWs& W,
+                                           int slices, int slice_elems, const RowScale& rs, const RowConst& rc,
+                                           float kf_row, int lo, int hi, bool cut, float top_p)
 {
-    __shared__ double scratch[kWaves];
-    __shared__ int wave_cnt[kWaves];
-    __shared__ unsigned cand_base;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long r = blockIdx.x / slices;
-    const int slice = blockIdx.x % slices;
-    const RowWs W = row_ws(ws, r, slices);
-    const RowCut cutv = *W.cut;
-    if (cutv.done)
-        return;
-    const float* __restrict__ x = sp.logits + r * sp.stride;
-    const SliceRange g = slice_range(slice, slice_elems, (int)sp.vocab);
-    const RowConst rc = row_const(sp.temperature[r]);
-    RowScale rs;
-    rs.max_x = cutv.max_x;
-    rs.c_hi = rc.c_hi;
-    rs.c_lo = rc.c_lo;
-    const int lo = cutv.lo, hi = cutv.hi;
-    // Bin tests without forming the bin: with t = x c16, bin(x) < lo  <=>  floor(t) > kf_row - lo
-    // <=>  t >= kf_row - lo + 1 (both sides of the middle inequality are integers); likewise
-    // bin(x) <= hi  <=>  t >= kf_row - hi.  The clamps of the bin only matter at the ends:
-    // lo == kBins keeps everything, hi == kBins - 1 makes every remaining element a candidate.
-    const float t_above = lo >= kBins ? -INFINITY : cutv.kf_row - (float)lo + 1.f;
-    const float t_cand = hi >= kBins - 1 ? -INFINITY : cutv.kf_row - (float)hi;
-
-    float xv[32];
-    SPD_LOAD_SLICE(xv, x, g, tid)
-
-    int ncand = 0;
-    double above = 0.0;
-    float all32 = 0.f;  // this thread's 32 probabilities; widened once
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        float s_above = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float xq = xv[4 * j + k];
-            if (xq == -INFINITY)
-                continue;
-            const float p = prob(xq, rs);
-            all32 += p;
-            const float t = xq * rc.c16;
-            if (t >= t_above)
-                s_above += p;
-            else if (t >= t_cand)
-                ++ncand;
-        }
-        // 256 fp32 terms per segment; the segment sums are widened before they are combined
-        for (int o = 32; o > 0; o >>= 1)
-            s_above += __shfl_xor(s_above, o);
-        if (lane == 0) {
-            W.seg[(size_t)slice * kSegPerSlice + j * kWaves + wave] = (double)s_above;
-            above += (double)s_above;
-        }
-    }
-    double mass = (double)all32;
-    // tail logits (thread 0): counted in the slice mass, always sent as candidates when kept at all
-    int tail_cand = 0;
-    if (tid == 0)
-        for (int k = 0; k < g.ntail; ++k) {
-            const float xt = x[g.v4end + k];
-            mass += (double)prob(xt, rs);
-            if (bin_below(cutv.kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins)
-                ++tail_cand;
-        }
-    ncand += tail_cand;
-    mass = block_sum_f64(mass, scratch);
-    above = block_sum_f64(above, scratch);
-
-    int incl = ncand;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(incl, o);
-        if (lane >= o)
-            incl += up;
-    }
-    __syncthreads();
-    if (lane == 63)
-        wave_cnt[wave] = incl;
-    __syncthreads();
-    int wave_off = 0, block_total = 0;
-    for (int w = 0; w < kWaves; ++w) {
-        if (w < wave)
-            wave_off += wave_cnt[w];
-        block_total += wave_cnt[w];
-    }
-    if (tid == 0) {
-        cand_base = block_total ? atomicAdd(&W.cut->cand_total, (unsigned)block_total) : 0u;
-        SliceStat* st = stat_at(W, slice);
-        st->mass = mass;
-        st->above = above;
-    }
-    __syncthreads();
-    if (ncand) {
-        unsigned pos = cand_base + (unsigned)(wave_off + incl - ncand);
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const float xq = xv[q];
-            if (xq == -INFINITY)
-                continue;
-            const float t = xq * rc.c16;
-            if (t < t_above && t >= t_cand) {
-                if (pos < (unsigned)kCandCap)
-                    W.cand[pos] = (unsigned long long)__float_as_uint(xq) |
-                                  ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32);
-                ++pos;
-            }
-        }
-        if (tid == 0)
-            for (int k = 0; k < g.ntail; ++k) {
-                const float xt = x[g.v4end + k];
-                if (bin_below(cutv.kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins) {
-                    if (pos < (unsigned)kCandCap)
-                        W.cand[pos] = (unsigned long long)__float_as_uint(xt) |
-                                      ((unsigned long long)(unsigned)(g.v4end + k) << 32);
-                    ++pos;
-                }
-            }
-    }
-}
-
-// ---- kernel 4: exact threshold, CDF walk -----------------------------------------------------------------
-struct PickLds {
-    RowLds row;
-    unsigned long long cand[kCandCap];
-    double smass[kMaxSlices];
-    double sabove[kMaxSlices];
-};
-
-__global__ __launch_bounds__(kBlock) void sampler_pick_kernel(SamplerParams sp, char* ws, int slices,
-                                                              int slice_elems)
-{
-    __shared__ PickLds L;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long r = blockIdx.x;
-    const RowWs W = row_ws(ws, r, slices);
-    const RowCut cutv = *W.cut;
-    if (cutv.done)
-        return;
     const float* __restrict__ x = sp.logits + r * sp.stride;
     const int V = (int)sp.vocab;
-    const RowConst rc = row_const(sp.temperature[r]);
-    RowScale rs;
-    rs.max_x = cutv.max_x;
-    rs.c_hi = rc.c_hi;
-    rs.c_lo = rc.c_lo;
-    const int lo = cutv.lo, hi = cutv.hi;
-    const bool cut = lo < kBins;
-    const int C = (int)min(cutv.cand_total, (unsigned)kCandCap);
+    const unsigned cand_total = observe(&W.ctl->cand_total);
+    const int C = (int)min(cand_total, (unsigned)kCandCap);
     const int nseg = slices * kSegPerSlice;
     double* seg_mass = L.row.seg_mass;
-
-    // everything this kernel needs from memory, fetched in one round
     if (tid < slices) {
         const SliceStat* st = stat_at(W, tid);
-        L.smass[tid] = st->mass;
-        L.sabove[tid] = st->above;
+        L.smass[tid] = observe(&st->mass);
+        L.sabove[tid] = observe(&st->above);
     }
     for (int i = tid; i < C; i += kBlock)
-        L.cand[i] = W.cand[i];
+        L.cand[i] = observe(&W.cand[i]);
     for (int sidx = tid; sidx < nseg; sidx += kBlock)
-        seg_mass[sidx] = W.seg[sidx];
+        seg_mass[sidx] = observe(&W.seg[sidx]);
     __syncthreads();
     double S = 0.0, above_total = 0.0;
     for (int s = 0; s < slices; ++s) {
         S += L.smass[s];
         above_total += L.sabove[s];
     }
-    const double need = (double)sp.top_p[r] * S;
-
-    // candidate masses by the definition of p_i (deterministic tree)
-    double cm = 0.0;
-    for (int i = tid; i < C; i += kBlock)
-        cm += (double)prob(__uint_as_float((unsigned)L.cand[i]), rs);
-    cm = block_sum_f64(cm, L.row.scratch);
+    const double need = (double)top_p * S;
 
     uint32_t key_tau = 0u;
-    double Z = above_total + cm;
+    double Z = above_total;
     if (cut) {
-        // the cut must fall among the candidates; otherwise redo the row the slow way
-        if (cutv.cand_total > (unsigned)kCandCap || !(above_total < need) || !(above_total + cm >= need)) {
+        // Radix select over the candidates' order keys, taken relative to the largest one
+        // (rel = kmax - key, 0 = most probable) so that only the bits in which the candidates
+        // differ are resolved: 11 bits per level, usually two levels.
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        for (int i = tid; i < C; i += kBlock) {
+            const uint32_t key = order_key(__uint_as_float((unsigned)L.cand[i]));
+            kmin = min(kmin, key);
+            kmax = max(kmax, key);
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+        }
+        if (lane == 0) {
+            L.kmin[wave] = kmin;
+            L.kmax[wave] = kmax;
+        }
+        double* H = L.row.hist;
+        for (int b = tid; b < kBins; b += kBlock)
+            H[b] = 0.0;
+        __syncthreads();
+        for (int w = 0; w < kWaves; ++w) {
+            kmin = min(kmin, L.kmin[w]);
+            kmax = max(kmax, L.kmax[w]);
+        }
+        const uint32_t span = C > 0 ? kmax - kmin : 0u;
+        const int nbits = span ? 32 - __clz((int)span) : 1;
+        uint32_t prefix = 0u;
+        double abv = above_total;
+        bool bad = cand_total > (unsigned)kCandCap || !(above_total < need);
+        for (int shift = 11 * ((nbits - 1) / 11); shift >= 0 && !bad; shift -= 11) {
+            for (int i = tid; i < C; i += kBlock) {
+                const float xc = __uint_as_float((unsigned)L.cand[i]);
+                const uint32_t rel = kmax - order_key(xc);
+                if ((uint64_t)rel >> (shift + 11) == prefix)
+                    atomicAdd(&H[rank_slot((rel >> shift) & 0x7ffu)], (double)prob(xc, rs));
+            }
+            __syncthreads();
+            const BinPick pk = wave_pick(H, abv, need, false);
+            // the cut must fall among the candidates
+            if (shift == 11 * ((nbits - 1) / 11) && !(above_total + pk.total >= need))
+                bad = true;
+            prefix = (prefix << 11) | (uint32_t)pk.bin;
+            abv = pk.above;
+            Z = pk.above + pk.in_bin;
+            __syncthreads();
+            if (shift > 0) {
+                for (int b = tid; b < kBins; b += kBlock)
+                    H[b] = 0.0;
+                __syncthreads();
+            }
+        }
+        if (bad) {
+            // candidate overflow or an estimate that missed the cut: redo the row the slow way
             sample_row_from_memory(sp, r, L.row);
             return;
         }
-        // radix select over the candidates' order keys: 11 + 11 + 10 bits
-        double* H = L.row.hist;
-        uint32_t prefix = 0u;
-        double above = above_total;
-        for (int level = 0; level < 3; ++level) {
-            const int shift = level == 0 ? 21 : level == 1 ? 10 : 0;
-            const int bits = level == 2 ? 10 : 11;
-            for (int b = tid; b < kBins; b += kBlock)
-                H[b] = 0.0;
-            __syncthreads();
-            for (int i = tid; i < C; i += kBlock) {
-                const float xc = __uint_as_float((unsigned)L.cand[i]);
-                const uint32_t key = order_key(xc);
-                if (level == 0 || (key >> (shift + bits)) == prefix)
-                    atomicAdd(&H[(key >> shift) & ((1u << bits) - 1u)], (double)prob(xc, rs));
-            }
-            __syncthreads();
-            pick_bin(H, above, need, &L.row.sh_bin, &L.row.sh_low, &L.row.sh_above, L.row.scratch);
-            prefix = (prefix << bits) | (uint32_t)L.row.sh_bin;
-            above = L.row.sh_above;
-            __syncthreads();
-        }
-        key_tau = prefix;
-        double kept = 0.0;
-        for (int i = tid; i < C; i += kBlock) {
-            const float xc = __uint_as_float((unsigned)L.cand[i]);
-            if (order_key(xc) >= key_tau)
-                kept += (double)prob(xc, rs);
-        }
-        Z = above_total + block_sum_f64(kept, L.row.scratch);
+        key_tau = kmax - prefix;
     }
 
     // kept candidates join their segments (vocabulary order)
@@ -1037,7 +1018,7 @@ __global__ __launch_bounds__(kBlock) void sampler_pick_kernel(SamplerParams sp, 
                 keep[k] = false;
                 if (i < end) {
                     const float xi = x[i];
-                    const int b = bin_below(cutv.kf_row, bin_coord(xi, rc.c16));
+                    const int b = bin_below(kf_row, bin_coord(xi, rc.c16));
                     if (b < lo || (b <= hi && order_key(xi) >= key_tau)) {
                         pk[k] = prob(xi, rs);
                         keep[k] = true;
@@ -1072,6 +1053,247 @@ __global__ __launch_bounds__(kBlock) void sampler_pick_kernel(SamplerParams sp, 
     }
 }
 
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void sampler_select_kernel(SamplerParams sp, char* ws, int slices,
+                                                                int slice_elems, int cut_ready)
+{
+    __shared__ SelectLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long r = blockIdx.x / slices;
+    const int slice = blockIdx.x % slices;
+    const RowWs W = row_ws(ws, r, slices);
+    const float* __restrict__ x = sp.logits + r * sp.stride;
+    const int V = (int)sp.vocab;
+    const SliceRange g = slice_range(slice, slice_elems, V);
+    const float T = sp.temperature[r];
+    const bool greedy = (T == 0.f);
+    const float top_p = sp.top_p[r];
+    const bool cut = !greedy && top_p < 1.f;
+
+    // The slice statistics are requested first and the slice's logits right behind them (loads
+    // return in order); the row's cut is worked out while the logits travel.
+    float st_max = -INFINITY;
+    int st_arg = 0x7fffffff;
+    int lo = kBins, hi = kBins;  // candidate bins, counted down from the maximum's bin; kBins = no cut
+    if (cut && cut_ready) {
+        lo = W.ctl->lo;
+        hi = W.ctl->hi;
+    }
+    if (tid < slices) {
+        const SliceStat* st = stat_at(W, tid);
+        st_max = st->max_x;
+        st_arg = st->argmax;
+    }
+    float xv[32];
+    {
+        // a greedy row needs no second look: all its loads collapse onto one float4
+        SliceRange gl = g;
+        if (greedy)
+            gl.v4end = gl.e0 + 4;
+        SPD_LOAD_SLICE(xv, x, gl, tid)
+    }
+    if (tid < slices) {
+        L.smax[tid] = st_max;
+        L.sarg[tid] = st_arg;
+    }
+    __syncthreads();
+    float M = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int s = 0; s < slices; ++s) {
+        if (L.smax[s] > M || (L.smax[s] == M && L.sarg[s] < arg)) {
+            M = L.smax[s];
+            arg = L.sarg[s];
+        }
+    }
+    if (greedy) {
+        if (slice == 0 && tid == 0)
+            sp.tokens[r] = arg == 0x7fffffff ? 0 : arg;
+        return;
+    }
+    const RowConst rc = row_const(T);
+    const float kf_row = bin_coord(M, rc.c16);
+    if (cut && !cut_ready) {
+        const CutBins cb = estimate_cut(L, W, slices, kf_row, rc, top_p);
+        lo = cb.lo;
+        hi = cb.hi;
+    }
+
+    SPD_MASK_SLICE(xv, g, tid)
+    RowScale rs;
+    rs.max_x = M;
+    rs.c_hi = rc.c_hi;
+    rs.c_lo = rc.c_lo;
+    // Bin tests without forming the bin: with t = x c16, bin(x) < lo  <=>  floor(t) > kf_row - lo
+    // <=>  t >= kf_row - lo + 1 (both sides of the middle inequality are integers); likewise
+    // bin(x) <= hi  <=>  t >= kf_row - hi.  The clamps of the bin only matter at the ends:
+    // lo == kBins keeps everything, hi == kBins - 1 makes every remaining element a candidate.
+    const float t_above = lo >= kBins ? -INFINITY : kf_row - (float)lo + 1.f;
+    const float t_cand = hi >= kBins - 1 ? -INFINITY : kf_row - (float)hi;
+
+    int ncand = 0;
+    double above = 0.0;
+    float all32 = 0.f;  // this thread's 32 probabilities; widened once
+    float s_above[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        s_above[j] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float xq = xv[4 * j + k];
+            if (xq == -INFINITY)
+                continue;
+            const float pq = prob(xq, rs);
+            all32 += pq;
+            const float t = xq * rc.c16;
+            if (t >= t_above)
+                s_above[j] += pq;
+            else if (t >= t_cand)
+                ++ncand;
+        }
+    }
+    // 256 fp32 terms per segment.  The eight wavefront reductions are folded: after the exchange
+    // across 32 lanes each half keeps four segments, then two, then one, so that lane 8 s ends
+    // up with the sum of segment s (10 exchanges instead of 48).
+    {
+        const bool up32 = (lane & 32) != 0, up16 = (lane & 16) != 0, up8 = (lane & 8) != 0;
+        float a4[4], a2[2], a1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float keep = up32 ? s_above[4 + j] : s_above[j];
+            const float give = up32 ? s_above[j] : s_above[4 + j];
+            a4[j] = keep + __shfl_xor(give, 32);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float keep = up16 ? a4[2 + j] : a4[j];
+            const float give = up16 ? a4[j] : a4[2 + j];
+            a2[j] = keep + __shfl_xor(give, 16);
+        }
+        {
+            const float keep = up8 ? a2[1] : a2[0];
+            const float give = up8 ? a2[0] : a2[1];
+            a1 = keep + __shfl_xor(give, 8);
+        }
+        a1 += __shfl_xor(a1, 4);
+        a1 += __shfl_xor(a1, 2);
+        a1 += __shfl_xor(a1, 1);
+        // lane 8 s (and its seven neighbours) holds segment j = 4 (lane/32) + 2 (lane/16 % 2) + lane/8 % 2
+        if ((lane & 7) == 0) {
+            const int j = lane >> 3;
+            publish(&W.seg[(size_t)slice * kSegPerSlice + j * kWaves + wave], (double)a1);
+            above = (double)a1;
+        }
+    }
+    double mass = (double)all32;
+    // tail logits (thread 0): counted in the slice mass, always sent as candidates when kept at all
+    int tail_cand = 0;
+    if (tid == 0)
+        for (int k = 0; k < g.ntail; ++k) {
+            const float xt = x[g.v4end + k];
+            mass += (double)prob(xt, rs);
+            if (bin_below(kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins)
+                ++tail_cand;
+        }
+    ncand += tail_cand;
+    block_sum2_f64(mass, above, L.row.scratch);
+
+    int incl = ncand;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o)
+            incl += up;
+    }
+    __syncthreads();
+    if (lane == 63)
+        L.wave_cnt[wave] = incl;
+    __syncthreads();
+    int wave_off = 0, block_total = 0;
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave)
+            wave_off += L.wave_cnt[w];
+        block_total += L.wave_cnt[w];
+    }
+    if (tid == 0) {
+        L.cand_base = block_total ? __hip_atomic_fetch_add(&W.ctl->cand_total, (unsigned)block_total,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                  : 0u;
+        SliceStat* st = stat_at(W, slice);
+        publish(&st->mass, mass);
+        publish(&st->above, above);
+    }
+    __syncthreads();
+    if (ncand) {
+        unsigned pos = L.cand_base + (unsigned)(wave_off + incl - ncand);
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            const float xq = xv[q];
+            if (xq == -INFINITY)
+                continue;
+            const float t = xq * rc.c16;
+            if (t < t_above && t >= t_cand) {
+                if (pos < (unsigned)kCandCap)
+                    publish(&W.cand[pos],
+                            (unsigned long long)__float_as_uint(xq) |
+                                ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32));
+                ++pos;
+            }
+        }
+        if (tid == 0)
+            for (int k = 0; k < g.ntail; ++k) {
+                const float xt = x[g.v4end + k];
+                if (bin_below(kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins) {
+                    if (pos < (unsigned)kCandCap)
+                        publish(&W.cand[pos], (unsigned long long)__float_as_uint(xt) |
+                                                  ((unsigned long long)(unsigned)(g.v4end + k) << 32));
+                    ++pos;
+                }
+            }
+    }
+
+    if (cut_ready)
+        return;  // many workgroups per launch: the pick kernel finishes the rows
+
+    // ---- arrival: everything this workgroup published has been acknowledged before it counts ----
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0)
+        L.arrived_before = __hip_atomic_fetch_add(&W.ctl->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (L.arrived_before != (unsigned)(slices - 1))
+        return;
+    // last workgroup of the row
+    finish_row(L, sp, r, W, slices, slice_elems, rs, rc, kf_row, lo, hi, cut, top_p);
+}
+
+// The finishing step as a kernel of its own, for launches with many workgroups: there the select
+// kernel's workgroups neither wait for their stores to be acknowledged nor count arrivals.
+__global__ __launch_bounds__(kBlock) void sampler_pick_kernel(SamplerParams sp, char* ws, int slices,
+                                                              int slice_elems)
+{
+    __shared__ SelectLds L;
+    const int tid = threadIdx.x;
+    const long long r = blockIdx.x;
+    const RowWs W = row_ws(ws, r, slices);
+    const float T = sp.temperature[r];
+    if (T == 0.f)
+        return;  // greedy rows were answered by the select kernel
+    const float top_p = sp.top_p[r];
+    const bool cut = top_p < 1.f;
+    if (tid < slices)
+        L.smax[tid] = stat_at(W, tid)->max_x;
+    __syncthreads();
+    float M = -INFINITY;
+    for (int s = 0; s < slices; ++s)
+        M = fmaxf(M, L.smax[s]);
+    const RowConst rc = row_const(T);
+    RowScale rs;
+    rs.max_x = M;
+    rs.c_hi = rc.c_hi;
+    rs.c_lo = rc.c_lo;
+    const int lo = cut ? W.ctl->lo : kBins, hi = cut ? W.ctl->hi : kBins;
+    finish_row(L, sp, r, W, slices, slice_elems, rs, rc, bin_coord(M, rc.c16), lo, hi, cut, top_p);
+}
+
+
 __global__ __launch_bounds__(kBlock) void sample_rows_kernel(SamplerParams sp)
 {
     __shared__ RowLds lds;
@@ -1104,17 +1326,26 @@ hipError_t launch_sampler(const SamplerParams& p, void* ws, hipStream_t s)
 {
     const int slices = sampler_slices(p.rows, p.vocab);
     const bool aligned = (p.stride % 4 == 0) && ((uintptr_t)p.logits % 16 == 0);
-    if (slices == 0 || !aligned) {
+    if (slices == 0 || !aligned || p.vocab < 4) {
         hipLaunchKernelGGL(sample_rows_kernel, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p);
         return hipGetLastError();
     }
     int slice_elems = (int)((p.vocab + slices - 1) / slices);
     slice_elems = (slice_elems + 3) / 4 * 4;
-    const dim3 per_slice((unsigned)(p.rows * slices)), per_row((unsigned)p.rows), block(kBlock);
+    const dim3 per_slice((unsigned)(p.rows * slices)), block(kBlock);
     hipLaunchKernelGGL(sampler_hist_kernel, per_slice, block, 0, s, p, (char*)ws, slices, slice_elems);
-    hipLaunchKernelGGL(sampler_cut_kernel, per_row, block, 0, s, p, (char*)ws, slices);
-    hipLaunchKernelGGL(sampler_mass_kernel, per_slice, block, 0, s, p, (char*)ws, slices, slice_elems);
-    hipLaunchKernelGGL(sampler_pick_kernel, per_row, block, 0, s, p, (char*)ws, slices, slice_elems);
+    // With many workgroups per launch the cut estimate is computed once per row instead of in
+    // every workgroup of the row, and the rows are finished by a kernel of their own: four
+    // kernels whose workgroups are short, instead of two whose workgroups wait on one another's
+    // results.
+    const int cut_ready = p.rows * slices > 2048 ? 1 : 0;
+    if (cut_ready)
+        hipLaunchKernelGGL(sampler_cut_kernel, dim3((unsigned)p.rows), block, 0, s, p, (char*)ws, slices);
+    hipLaunchKernelGGL(sampler_select_kernel, per_slice, block, 0, s, p, (char*)ws, slices, slice_elems,
+                       cut_ready);
+    if (cut_ready)
+        hipLaunchKernelGGL(sampler_pick_kernel, dim3((unsigned)p.rows), block, 0, s, p, (char*)ws, slices,
+                           slice_elems);
     return hipGetLastError();
 }
 
