@@ -24,6 +24,15 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
+# HBM-side traffic per launch (bytes) from hardware counters: rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for an
+# elementwise kernel of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this
+# machine).  Keyed by (kernel, workload); anything not listed is reported as null.  The entry
+# must be dropped when the kernel changes.  Source: profiles/hbm_traffic_cfg3_pmc.txt
+TRAFFIC_BYTES = {
+    ("suffix", "cfg3-bf16-p8192-n64"): int((76975.6 * 2.0 + 3009.0) * 1024),
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -34,6 +43,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=50)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -108,6 +119,17 @@ def main() -> int:
             lay[i % len(lay)].run(mask)
         return fn
 
+    # merge: every valid partial state is read once (fp32 accumulator + (m, l)), the output written
+    plan = B.spd_attn_plan(sets[0][0][0].desc, first.max_prefix_len, first.max_suffix_len)
+    split_tok, _, chunk_tok, _ = plan
+    rows_q = sp.num_q_heads
+    n_partials = 0
+    for b in range(sp.num_prompts):
+        nsamp = int(first.sample_indptr[b + 1] - first.sample_indptr[b])
+        n_partials += nsamp * rows_q * -(-int(first.prefix_lens[b]) // split_tok)
+    n_partials += rows_q * int(sum(-(-int(l) // chunk_tok) for l in first.suffix_lens))
+    merge_bytes = n_partials * (sp.head_dim + 2) * 4 + q_bytes
+
     it = args.kernel_iters
     us = {
         "prefix": time_stage(attn_stage(B.STAGE_PREFIX), it),
@@ -121,24 +143,37 @@ def main() -> int:
                    "TFLOPs": prefix_flops / us["prefix"] / 1e6, "calls_per_step": sp.layers},
         "suffix": {"us": us["suffix"], "bytes": suffix_bytes + q_bytes,
                    "GBps": (suffix_bytes + q_bytes) / us["suffix"] / 1e3, "calls_per_step": sp.layers},
-        "merge": {"us": us["merge"], "calls_per_step": sp.layers},
+        "merge": {"us": us["merge"], "bytes": merge_bytes, "GBps": merge_bytes / us["merge"] / 1e3,
+                  "calls_per_step": sp.layers},
         "sampler": {"us": us["sampler"], "bytes": sampler_bytes,
                     "GBps": sampler_bytes / us["sampler"] / 1e3, "calls_per_step": 1},
     }
     for k in kernels.values():
         k["frac_hbm_peak"] = k.get("GBps", 0.0) / HBM_PEAK_GBS
     kernels["prefix"]["frac_mfma_peak"] = kernels["prefix"]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
-    per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items()}
+    # the dominant kernel is looked for among the stages that are one kernel each; the sampler
+    # stage is two to four kernels (its event time is their sum) and is listed under "kernels"
+    per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items() if k in ("prefix", "suffix")}
     dom = max(per_step, key=per_step.get)
     if dom == "prefix" and prefix_flops / MFMA_BF16_PEAK_TFLOPS / 1e12 > (prefix_bytes + q_bytes) / HBM_PEAK_GBS / 1e9:
         roofline = {"kernel": "prefix", "bound": "mfma", "achieved": kernels["prefix"]["TFLOPs"],
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": kernels["prefix"]["frac_mfma_peak"], "traffic": None}
+                    "frac": kernels["prefix"]["frac_mfma_peak"],
+                    "traffic": TRAFFIC_BYTES.get(("prefix", sp.name))}
     else:
-        if dom == "merge":
-            dom = "suffix"
         roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"], "traffic": None}
+                    "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"],
+                    "traffic": TRAFFIC_BYTES.get((dom, sp.name))}
+
+    if args.calibrate_copy:
+        # a plain elementwise kernel of known size in the same process: 256 MiB read and 256 MiB
+        # written per call (torch's out-of-place multiply; a tensor copy would go to the runtime's
+        # blit path instead of a kernel of known shape)
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
 
     # ---- CPU baseline: the fp64 checker on the same workload ---------------------------------
     cpu = None
