@@ -128,7 +128,8 @@ def main() -> int:
         nsamp = int(first.sample_indptr[b + 1] - first.sample_indptr[b])
         n_partials += nsamp * rows_q * -(-int(first.prefix_lens[b]) // split_tok)
     n_partials += rows_q * int(sum(-(-int(l) // chunk_tok) for l in first.suffix_lens))
-    merge_bytes = n_partials * (sp.head_dim + 2) * 4 + q_bytes
+    part_elt = 2 if sp.dtype == "bf16" else 4  # stored partial outputs: fp16 on the bf16 path
+    merge_bytes = n_partials * (sp.head_dim * part_elt + 8) + q_bytes
 
     it = args.kernel_iters
     us = {

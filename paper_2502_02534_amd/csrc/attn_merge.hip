@@ -1,12 +1,16 @@
 // Log-sum-exp merge of partial softmax states (prefix splits and suffix chunks) into
-// the normalised attention output.  With states (m_i, l_i, acc_i):
-//   m = max m_i,  l = sum l_i 2^(m_i - m),  out = sum acc_i 2^(m_i - m) / l,
+// the normalised attention output.  With states (m_i, l_i, out_i = acc_i / l_i):
+//   m = max m_i,  w_i = l_i 2^(m_i - m),  l = sum w_i,  out = sum w_i out_i / l,
 //   lse = (m + log2 l) ln 2.
 // This is the rescaling step of the paper's online-softmax recurrence (App., attn
 // task 2: `ExpMaxDiff`, `WeightedSumSingle`, `WeightedSumDouble`, `Div`) applied to
 // blocks instead of single tokens.  Empty ranges are skipped, so the initial state
 // (-inf, 0, 0) is the identity.
 #include "spd_internal.h"
+
+#include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 namespace spd {
 namespace {
@@ -24,14 +28,33 @@ constexpr int kMergeThreads = 256;
 constexpr int kMaxSlots = 128;   // prefix splits + suffix chunks (each at most 64)
 
 // One workgroup merges kMergeThreads / (D/4) rows; a thread owns 4 channels of one row.
-// Step 1 puts every valid partial's (m, l) in LDS, step 2 turns them into weights
-// 2^(m_i - m) (0 for empty partials) and the row's m and l, step 3 combines the accumulators,
-// whose loads (up to 32 independent 16-byte loads per thread) were issued before step 1.
+// The threads of a row share out the (m, l) pairs, find the row's m and l with shuffles and
+// leave the weights l_i 2^(m_i - m) (0 for empty partials) in LDS; then every thread combines
+// the partial outputs, whose loads (up to 32 independent loads per thread) were issued first.
+// HALF: the partial outputs are fp16 (8 bytes per thread and partial) instead of fp32 (16).
+template <bool HALF> struct PartVec;
+template <> struct PartVec<false> {
+    typedef float4 type;
+    static __device__ __forceinline__ float4 zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ float4 widen(float4 v) { return v; }
+};
+template <> struct PartVec<true> {
+    typedef uint2 type;
+    static __device__ __forceinline__ uint2 zero() { return make_uint2(0u, 0u); }
+    static __device__ __forceinline__ float4 widen(uint2 v)
+    {
+        const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&v.x));
+        const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&v.y));
+        return make_float4(a.x, a.y, b.x, b.y);
+    }
+};
+
+template <bool HALF>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p, int tpr /* threads per row */)
 {
-    __shared__ float2 ml[kMergeThreads / 8][kMaxSlots];   // at most 32 rows per block (D = 32)
-    __shared__ float wgt[kMergeThreads / 8][kMaxSlots];
-    __shared__ float row_m[kMergeThreads / 8], row_l[kMergeThreads / 8];
+    typedef typename PartVec<HALF>::type vec_t;
+    typedef typename std::conditional<HALF, __half, float>::type elem_t;
+    __shared__ float wgt[kMergeThreads / 8][kMaxSlots];  // at most 32 rows per block (D = 32)
 
     const int rows_per_block = kMergeThreads / tpr;
     const int r_in = threadIdx.x / tpr;
@@ -50,56 +73,66 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
     }
     const int cnt = np + ns;
     const bool ch_ok = row_ok && 4 * c < p.D;
-    const float* base = p.part_acc + part_index(p, row_ok ? row : 0, 0) * p.D + 4 * c;
+    const elem_t* base = (const elem_t*)p.part_acc + part_index(p, row_ok ? row : 0, 0) * p.D + 4 * c;
     auto slot_at = [&](int i) { return i < np ? i : p.num_prefix_splits + (i - np); };
     // The first batch of accumulator loads does not need the weights: it is issued together
     // with the (m, l) loads so that both round trips overlap.
     constexpr int kBatch = 32;
-    float4 v[kBatch];
+    vec_t v[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[u] = PartVec<HALF>::zero();
         if (ch_ok && u < cnt)
-            v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_at(u) * p.D);
+            v[u] = *reinterpret_cast<const vec_t*>(base + (long long)slot_at(u) * p.D);
     }
-    for (int i = c; i < cnt; i += tpr)
-        ml[r_in][i] = p.part_ml[part_index(p, row, slot_at(i))];
-    __syncthreads();
-    if (c == 0) {
-        float m = -INFINITY;
-        for (int i = 0; i < cnt; ++i)
-            m = fmaxf(m, ml[r_in][i].x);
-        float l = 0.f;
-        for (int i = 0; i < cnt; ++i) {
-            const float2 mv = ml[r_in][i];
-            const float w = mv.y > 0.f ? __builtin_amdgcn_exp2f(mv.x - m) : 0.f;
+    // Weights: the tpr threads of a row (a power of two <= 64, aligned inside a wavefront) each
+    // take every tpr-th partial; maximum and sum go round the group with shuffles.
+    constexpr int kPerLane = kMaxSlots / 8;
+    float2 mine[kPerLane];
+    float m = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kPerLane; ++k) {
+        const int i = c + k * tpr;
+        mine[k] = make_float2(-INFINITY, 0.f);
+        if (i < cnt)
+            mine[k] = p.part_ml[part_index(p, row, slot_at(i))];
+        if (mine[k].y > 0.f)
+            m = fmaxf(m, mine[k].x);
+    }
+    for (int o = tpr >> 1; o > 0; o >>= 1)
+        m = fmaxf(m, __shfl_xor(m, o));
+    float l = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPerLane; ++k) {
+        const int i = c + k * tpr;
+        const float w = mine[k].y > 0.f ? mine[k].y * __builtin_amdgcn_exp2f(mine[k].x - m) : 0.f;
+        if (i < cnt)
             wgt[r_in][i] = w;
-            l = fmaf(mv.y, w, l);
-        }
-        row_m[r_in] = m;
-        row_l[r_in] = l;
+        l += w;
     }
+    for (int o = tpr >> 1; o > 0; o >>= 1)
+        l += __shfl_xor(l, o);
     __syncthreads();
     if (!ch_ok)
         return;
-    const float l = row_l[r_in];
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i0 = 0; i0 < cnt; i0 += kBatch) {
         if (i0 > 0) {
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                v[u] = PartVec<HALF>::zero();
                 if (i0 + u < cnt)
-                    v[u] = *reinterpret_cast<const float4*>(base + (long long)slot_at(i0 + u) * p.D);
+                    v[u] = *reinterpret_cast<const vec_t*>(base + (long long)slot_at(i0 + u) * p.D);
             }
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const float w = i0 + u < cnt ? wgt[r_in][i0 + u] : 0.f;
-            acc.x = fmaf(v[u].x, w, acc.x);
-            acc.y = fmaf(v[u].y, w, acc.y);
-            acc.z = fmaf(v[u].z, w, acc.z);
-            acc.w = fmaf(v[u].w, w, acc.w);
+            const float4 f = PartVec<HALF>::widen(v[u]);
+            acc.x = fmaf(f.x, w, acc.x);
+            acc.y = fmaf(f.y, w, acc.y);
+            acc.z = fmaf(f.z, w, acc.z);
+            acc.w = fmaf(f.w, w, acc.w);
         }
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -116,7 +149,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
         *reinterpret_cast<uint2*>((uint16_t*)p.out + row * p.D + 4 * c) = o;
     }
     if (p.lse && c == 0)
-        p.lse[row] = l > 0.f ? (row_m[r_in] + __log2f(l)) * kLn2 : -INFINITY;
+        p.lse[row] = l > 0.f ? (m + __log2f(l)) * kLn2 : -INFINITY;
 }
 
 }  // namespace
@@ -130,7 +163,10 @@ hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s)
     const int rows_per_block = kMergeThreads / use;
     const long long total = (long long)p.N * p.Hq;
     const dim3 grid((unsigned)((total + rows_per_block - 1) / rows_per_block));
-    hipLaunchKernelGGL(attn_merge_kernel, grid, dim3(kMergeThreads), 0, s, p, use);
+    if (p.part_half)
+        hipLaunchKernelGGL(attn_merge_kernel<true>, grid, dim3(kMergeThreads), 0, s, p, use);
+    else
+        hipLaunchKernelGGL(attn_merge_kernel<false>, grid, dim3(kMergeThreads), 0, s, p, use);
     return hipGetLastError();
 }
 

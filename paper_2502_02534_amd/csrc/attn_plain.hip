@@ -5,6 +5,8 @@
 // and the weighted value rows are accumulated with lanes striding the channels.
 #include "spd_internal.h"
 
+#include <hip/hip_fp16.h>
+
 namespace spd {
 namespace {
 
@@ -108,12 +110,16 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnParams p, int slot0,
         }
     }
     const long long prow = part_index(p, row, slot0 + part);
-    float* dst = p.part_acc + prow * D;
+    const float inv_l = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
     for (int i = 0; i < kMaxChanPerLane; ++i) {
         const int d = lane + 64 * i;
-        if (d < D)
-            dst[d] = acc[i];
+        if (d < D) {
+            if (p.part_half)
+                ((__half*)p.part_acc)[prow * D + d] = __float2half(acc[i] * inv_l);
+            else
+                ((float*)p.part_acc)[prow * D + d] = acc[i] * inv_l;
+        }
     }
     if (lane == 0)
         p.part_ml[prow] = make_float2(m, l);

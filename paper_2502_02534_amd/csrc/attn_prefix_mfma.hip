@@ -26,6 +26,8 @@
 // paper's online-softmax recurrence (App., attn task 2).
 #include "spd_internal.h"
 
+#include <hip/hip_fp16.h>
+
 #include <utility>
 
 namespace spd {
@@ -406,14 +408,20 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams
     const long long prow = part_index(p, out_row, split);
     if (h == 0)
         p.part_ml[prow] = make_float2(m_run, l);
-    float* dst = p.part_acc + prow * kD;
+    // the split's own normalised output, fp16 (l > 0: a split holds at least one token)
+    const float inv_l = 1.f / l;
+    __half* dst = (__half*)p.part_acc + prow * kD;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             // registers 4 q4 .. 4 q4 + 3 are channels 32 db + 8 q4 + 4 h .. + 3
-            float4 v = make_float4(o[db][4 * q4], o[db][4 * q4 + 1], o[db][4 * q4 + 2], o[db][4 * q4 + 3]);
-            *reinterpret_cast<float4*>(dst + 32 * db + 8 * q4 + 4 * h) = v;
+            const __half2 lo = __floats2half2_rn(o[db][4 * q4] * inv_l, o[db][4 * q4 + 1] * inv_l);
+            const __half2 hi = __floats2half2_rn(o[db][4 * q4 + 2] * inv_l, o[db][4 * q4 + 3] * inv_l);
+            uint2 v;
+            v.x = *reinterpret_cast<const uint32_t*>(&lo);
+            v.y = *reinterpret_cast<const uint32_t*>(&hi);
+            *reinterpret_cast<uint2*>(dst + 32 * db + 8 * q4 + 4 * h) = v;
         }
 }
 

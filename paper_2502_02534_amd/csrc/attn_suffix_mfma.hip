@@ -19,6 +19,8 @@
 // recurrence (App., attn task 2): (m, l, unnormalised accumulator).
 #include "spd_internal.h"
 
+#include <hip/hip_fp16.h>
+
 namespace spd {
 namespace {
 
@@ -230,14 +232,26 @@ __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int
     const long long row0 = (long long)n * p.Hq + (long long)j * G;  // first of the G output rows
     if (r == 0 && c < G)
         p.part_ml[part_index(p, row0 + c, slot0 + chunk)] = make_float2(m_run, l_run);
+    // the chunk's own normalised output, fp16: accumulator register i of lane-row r belongs to
+    // query head 4 r + i, whose l sits in the lanes with c == 4 r + i
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int g = 4 * r + i;
+        const float lg = __shfl(l_run, g & 15);
         if (g < G) {
-            float* dst = p.part_acc + part_index(p, row0 + g, slot0 + chunk) * kD + 8 * c;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                dst[k] = o[k][i];
+            const float inv_l = 1.f / lg;  // > 0: the chunk holds at least one token
+            __half* dst = (__half*)p.part_acc + part_index(p, row0 + g, slot0 + chunk) * kD + 8 * c;
+            uint4 v;
+            __half2 h2;
+            h2 = __floats2half2_rn(o[0][i] * inv_l, o[1][i] * inv_l);
+            v.x = *reinterpret_cast<const uint32_t*>(&h2);
+            h2 = __floats2half2_rn(o[2][i] * inv_l, o[3][i] * inv_l);
+            v.y = *reinterpret_cast<const uint32_t*>(&h2);
+            h2 = __floats2half2_rn(o[4][i] * inv_l, o[5][i] * inv_l);
+            v.z = *reinterpret_cast<const uint32_t*>(&h2);
+            h2 = __floats2half2_rn(o[6][i] * inv_l, o[7][i] * inv_l);
+            v.w = *reinterpret_cast<const uint32_t*>(&h2);
+            *reinterpret_cast<uint4*>(dst) = v;
         }
     }
 }

@@ -11,10 +11,12 @@ namespace spd {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// Unnormalised partial softmax state of one (sample, query head) over a token range:
-// running maximum m (in base-2 units of the scaled score), sum l of 2^(s - m) and the
-// accumulator sum 2^(s - m) v.  This is the deferred-division form of the paper's
-// online-softmax recurrence (App., attn task 2).  An empty range has l == 0.
+// Partial softmax state of one (sample, query head) over a token range: running maximum m (in
+// base-2 units of the scaled score), sum l of 2^(s - m), and the range's own normalised output
+// sum 2^(s - m) v / l.  Inside a kernel the state is the deferred-division form of the paper's
+// online-softmax recurrence (App., attn task 2); the division by l happens once, when the state
+// is stored, which lets the bf16 path keep the stored output in fp16 (11 significant bits, three
+// more than the bf16 result it is merged into) at half the traffic.  An empty range has l == 0.
 struct AttnParams {
     int dtype, Hq, Hkv, D, G, B, N, max_spp, page_size;
     float scale_log2;  // sm_scale * log2(e)
@@ -34,7 +36,9 @@ struct AttnParams {
     int prefix_split_tokens, num_prefix_splits;
     int suffix_chunk_tokens, num_suffix_chunks;
     int num_slots;    // prefix splits + suffix chunks
-    float* part_acc;  // [N*Hq][slots][D]: a row's partial states are contiguous for the merge
+    void* part_acc;   // [N*Hq][slots][D] normalised partial outputs, fp16 if part_half else fp32;
+                      // a row's partial states are contiguous for the merge
+    int part_half;
     float2* part_ml;  // [N*Hq][slots]  (m, l)
     void* out;
     float* lse;

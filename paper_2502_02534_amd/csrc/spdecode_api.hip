@@ -75,13 +75,15 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
 #endif
     pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
     {
-        // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..512 tokens
+        // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..320 tokens
+        // (measured on ragged suffixes of up to 2048 tokens: 320-token chunks beat 512-token ones
+        // by 17 %, finer balance between wavefronts; the merge can take 64 chunks)
         const long long pairs = (long long)d->num_samples * d->num_kv_heads;
         const long long want_chunks = (2048 + pairs - 1) / pairs;
         long long t = (max_suffix + want_chunks - 1) / want_chunks;
         t = (t + 63) / 64 * 64;
         if (t < 64) t = 64;
-        if (t > 512) t = 512;
+        if (t > 320) t = 320;
         if (max_suffix > t * 64) t = part_tokens(max_suffix, 64, 64, 64);
 #ifdef SPD_TUNING
         if (const char* e = getenv("SPD_TUNE_SUFFIX_CHUNK")) t = atoi(e);
@@ -201,7 +203,8 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
     p.suffix_chunk_tokens = pl.suffix_chunk_tokens;
     p.num_suffix_chunks = pl.num_suffix_chunks;
     p.num_slots = pl.num_prefix_splits + pl.num_suffix_chunks;
-    p.part_acc = (float*)workspace;
+    p.part_acc = workspace;
+    p.part_half = desc->dtype == SPD_BF16 ? 1 : 0;
     p.part_ml = (float2*)((char*)workspace + pl.acc_bytes);
     p.out = out;
     p.lse = lse_out;

@@ -93,8 +93,16 @@ class DeviceSampler:
                         self.top_p, self.uniforms, self.tokens, self.workspace, stream)
 
 
-def upload_sampler(inp, device="cuda:0") -> DeviceSampler:
+def upload_sampler(inp, device="cuda:0", row_stride=None, pad_value=float("nan")) -> DeviceSampler:
+    """Uploads sampler inputs.  With `row_stride` > vocab the logits sit in a wider matrix whose
+    extra columns hold `pad_value` (the kernels must never read them as logits)."""
     rows, vocab = inp.logits.shape
     ws = torch.empty(max(256, B.sample_tokens_workspace_size(rows, vocab)), dtype=torch.uint8, device=device)
-    return DeviceSampler(_dev(inp.logits, device), _dev(inp.temperature, device), _dev(inp.top_p, device),
+    if row_stride is not None and row_stride != vocab:
+        wide = torch.full((rows, row_stride), pad_value, dtype=torch.float32, device=device)
+        wide[:, :vocab] = _dev(inp.logits, device)
+        logits = wide[:, :vocab]  # a view: stride(0) == row_stride
+    else:
+        logits = _dev(inp.logits, device)
+    return DeviceSampler(logits, _dev(inp.temperature, device), _dev(inp.top_p, device),
                          _dev(inp.uniforms, device), torch.empty(rows, dtype=torch.int32, device=device), ws)

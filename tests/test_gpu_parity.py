@@ -56,8 +56,8 @@ def check_attention(dev, oracle, inp, rows=None, stages=0):
     return err.max()
 
 
-def check_tokens(dev, oracle, sin):
-    ds = dev.upload_sampler(sin)
+def check_tokens(dev, oracle, sin, row_stride=None):
+    ds = dev.upload_sampler(sin, row_stride=row_stride, pad_value=1e30)
     ds.tokens.fill_(-7)
     ds.run()
     torch.cuda.synchronize()
@@ -125,14 +125,14 @@ def test_stage_masks_compose(dev, oracle):
     assert torch.equal(full.view(torch.int16), d.out.view(torch.int16))
 
 
-def _sampler_case(rows, vocab, sigma, T, top_p, seed, ties=False, stride_pad=0):
+def _sampler_case(rows, vocab, sigma, T, top_p, seed, ties=False):
     rng = np.random.default_rng(seed)
-    x = (rng.standard_normal((rows, vocab + stride_pad)) * sigma).astype(np.float32)
+    x = (rng.standard_normal((rows, vocab)) * sigma).astype(np.float32)
     if ties:
         x = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x))     # bf16-valued logits: many exact ties
     t = np.broadcast_to(np.asarray(T, np.float32), (rows,)).copy()
     tp = np.broadcast_to(np.asarray(top_p, np.float32), (rows,)).copy()
-    return W.SamplerInputs(x[:, :vocab] if stride_pad == 0 else x, t, tp, rng.random(rows, dtype=np.float32))
+    return W.SamplerInputs(x, t, tp, rng.random(rows, dtype=np.float32))
 
 
 SAMPLER_CASES = [
@@ -155,6 +155,14 @@ def test_sampler_cases(dev, oracle, i):
     print(f"sampler case {i}: {SAMPLER_CASES[i]}", flush=True)
     near_cdf, near_cut, mism = check_tokens(dev, oracle, _sampler_case(seed=500 + i, **SAMPLER_CASES[i]))
     print(f"  exempt near-CDF rows {near_cdf}, nucleus-ambiguous rows {near_cut}, differing tokens {mism}")
+
+
+@pytest.mark.parametrize("vocab,row_stride", [(20011, 20016), (20011, 20021), (32000, 32768), (4097, 4099)])
+def test_sampler_strided_rows(dev, oracle, vocab, row_stride):
+    """Rows that sit in a wider matrix: 16-byte aligned strides take the sliced kernels, the others
+    the whole-row kernel; the padding columns hold 1e30 and must never be read as logits."""
+    print(f"sampler strided vocab {vocab} stride {row_stride}", flush=True)
+    check_tokens(dev, oracle, _sampler_case(24, vocab, 3, 0.8, 0.9, 900 + row_stride), row_stride=row_stride)
 
 
 def test_sampler_mixed_per_row_parameters(dev, oracle):
