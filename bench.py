@@ -30,7 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # machine).  Keyed by (kernel, workload); anything not listed is reported as null.  The entry
 # must be dropped when the kernel changes.  Source: profiles/hbm_traffic_cfg3_pmc.txt
 TRAFFIC_BYTES = {
-    ("suffix", "cfg3-bf16-p8192-n64"): int((76975.6 * 2.0 + 3009.0) * 1024),
+    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95487.6 * 2.0 + 20031.5) * 1024),
+    ("prefix", "cfg3-bf16-p8192-n64"): int((18517.2 * 2.0 + 18433.6) * 1024),
+    ("suffix", "cfg3-bf16-p8192-n64"): int((76977.6 * 2.0 + 1593.0) * 1024),
 }
 
 
@@ -132,18 +134,32 @@ def main() -> int:
     merge_bytes = n_partials * (sp.head_dim * part_elt + 8) + q_bytes
 
     it = args.kernel_iters
+    # A step runs the prefix and the suffix pass in one launch when the library's fused kernel takes
+    # the shape (bf16, head_dim 128, more than 128 query rows per KV head, group size <= 16); the
+    # two passes are also timed as launches of their own for their separate rooflines.
+    max_rows = int(max(first.sample_indptr[b + 1] - first.sample_indptr[b] for b in range(sp.num_prompts))) * sp.group
+    fused = sp.dtype == "bf16" and sp.head_dim == 128 and max_rows > 128 and sp.group <= 16 and suffix_bytes > 0
     us = {
+        "attn_fused": time_stage(attn_stage(B.STAGE_PREFIX | B.STAGE_SUFFIX), it),
         "prefix": time_stage(attn_stage(B.STAGE_PREFIX), it),
         "suffix": time_stage(attn_stage(B.STAGE_SUFFIX), it),
         "merge": time_stage(attn_stage(B.STAGE_MERGE), it),
         "sampler": time_stage(lambda i: sets[i % copies][1].run(), it),
     }
+    attn_bytes = prefix_bytes + suffix_bytes + 2 * q_bytes
     kernels = {
+        "attn_fused": {"us": us["attn_fused"], "bytes": attn_bytes, "flops": prefix_flops,
+                       "GBps": attn_bytes / us["attn_fused"] / 1e3,
+                       "TFLOPs": prefix_flops / us["attn_fused"] / 1e6,
+                       "calls_per_step": sp.layers if fused else 0,
+                       "note": "prefix + suffix pass" + (" in one launch (what a step runs)" if fused
+                                                         else " as two launches back to back (what a step runs)")},
         "prefix": {"us": us["prefix"], "bytes": prefix_bytes + q_bytes, "flops": prefix_flops,
                    "GBps": (prefix_bytes + q_bytes) / us["prefix"] / 1e3,
-                   "TFLOPs": prefix_flops / us["prefix"] / 1e6, "calls_per_step": sp.layers},
+                   "TFLOPs": prefix_flops / us["prefix"] / 1e6, "calls_per_step": 0 if fused else sp.layers},
         "suffix": {"us": us["suffix"], "bytes": suffix_bytes + q_bytes,
-                   "GBps": (suffix_bytes + q_bytes) / us["suffix"] / 1e3, "calls_per_step": sp.layers},
+                   "GBps": (suffix_bytes + q_bytes) / us["suffix"] / 1e3,
+                   "calls_per_step": 0 if fused else sp.layers},
         "merge": {"us": us["merge"], "bytes": merge_bytes, "GBps": merge_bytes / us["merge"] / 1e3,
                   "calls_per_step": sp.layers},
         "sampler": {"us": us["sampler"], "bytes": sampler_bytes,
@@ -154,9 +170,15 @@ def main() -> int:
     kernels["prefix"]["frac_mfma_peak"] = kernels["prefix"]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
     # the dominant kernel is looked for among the stages that are one kernel each; the sampler
     # stage is two to four kernels (its event time is their sum) and is listed under "kernels"
-    per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items() if k in ("prefix", "suffix")}
+    per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items()
+                if k in ("attn_fused", "prefix", "suffix")}
     dom = max(per_step, key=per_step.get)
-    if dom == "prefix" and prefix_flops / MFMA_BF16_PEAK_TFLOPS / 1e12 > (prefix_bytes + q_bytes) / HBM_PEAK_GBS / 1e9:
+    if dom == "attn_fused" and prefix_flops / MFMA_BF16_PEAK_TFLOPS / 1e12 > attn_bytes / HBM_PEAK_GBS / 1e9:
+        roofline = {"kernel": "attn_fused", "bound": "mfma", "achieved": kernels["attn_fused"]["TFLOPs"],
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": kernels["attn_fused"]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": TRAFFIC_BYTES.get(("attn_fused", sp.name))}
+    elif dom == "prefix" and prefix_flops / MFMA_BF16_PEAK_TFLOPS / 1e12 > (prefix_bytes + q_bytes) / HBM_PEAK_GBS / 1e9:
         roofline = {"kernel": "prefix", "bound": "mfma", "achieved": kernels["prefix"]["TFLOPs"],
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": kernels["prefix"]["frac_mfma_peak"],

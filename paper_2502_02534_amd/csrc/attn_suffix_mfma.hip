@@ -1,259 +1,17 @@
-// Suffix pass (bf16, head_dim 128): streams each sample's private KV once.
-//
-// Work item = (sample n, KV head j, chunk of the suffix); one wavefront per item, four
-// independent items per workgroup (no workgroup barriers).  The G query heads that
-// share KV head j ride along as columns of one 16-wide MFMA tile, so the stream is
-// read once for all of them.  Per 32-token tile:
-//
-//   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = K rows (tokens) staged through LDS into
-//                 the operand layout, B = the G query rows (held in registers)
-//   online softmax in the base-2 domain on the accumulator registers; the accumulator
-//                 layout of S^T is exactly the A-operand layout of P, so P never moves
-//   O += P V      B = V transposed inside each lane with byte permutes (a lane loads the
-//                 same 16-byte column slice of 8 token rows and turns it into 8
-//                 token-contiguous fragments)
-//
-// Global loads are 16 bytes per lane with 16 adjacent lanes covering one 256-byte row.
-// The next tile's loads are issued before the current tile is computed.
-// The running state is the deferred-division form of the paper's online-softmax
-// recurrence (App., attn task 2): (m, l, unnormalised accumulator).
-#include "spd_internal.h"
-
-#include <hip/hip_fp16.h>
+// Suffix pass as a kernel of its own: launch wrapper around suffix_body.
+#include "attn_suffix_body.h"
 
 namespace spd {
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-
-constexpr int kD = 128;
-constexpr int kTile = 32;        // tokens per tile
-constexpr int kRowU4 = 17;       // LDS row: 16 x 16 B of data + 16 B pad
-constexpr int kWavesPerBlock = 4;
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
-{
-    return *reinterpret_cast<bf16x8*>(&v);
-}
-
-// Token (relative to the tile) that load slot s (0..7) of lane-row r (0..3) covers.
-// Slots 0..3 are tokens 4r..4r+3, slots 4..7 tokens 16+4r..16+4r+3: the same token
-// set, in the same order, that the accumulator of S^T hands lane-row r.
-__device__ __forceinline__ int tile_token(int r, int s) { return (s < 4 ? 0 : 12) + 4 * r + s; }
-
-__device__ __forceinline__ uint32_t dword(const uint4& v, int k)
-{
-    return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
-}
-
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-// Two floats to packed bf16 (round to nearest even): one v_cvt_pk_bf16_f32.
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    const bf16x2 r = __builtin_convertvector(v, bf16x2);
-    return *reinterpret_cast<const uint32_t*>(&r);
-}
+using namespace suffix_impl;
 
 template <bool PAGED>
 __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int slot0)
 {
     __shared__ uint4 ksm[kWavesPerBlock][kTile][kRowU4];
-
-    const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r = lane >> 4, c = lane & 15;
-    const int nc = p.num_suffix_chunks;
-    const long long item = (long long)blockIdx.x * kWavesPerBlock + wave;
-    const long long total = (long long)p.N * p.Hkv * nc;
-    if (item >= total)
-        return;
-    // KV head fastest: the waves of a workgroup (and neighbouring workgroups) read the heads of
-    // the same tokens at the same time, i.e. one contiguous stretch of the [token][head][D] cache
-    const int j = (int)(item % p.Hkv);
-    const int chunk = (int)((item / p.Hkv) % nc);
-    const int n = (int)(item / ((long long)nc * p.Hkv));
-    const int Ls = p.suffix_lens[n];
-    const int t0 = chunk * p.suffix_chunk_tokens;
-    const int t1 = min(Ls, t0 + p.suffix_chunk_tokens);
-    if (t0 >= t1)
-        return;
-    const int G = p.G;
-
-    const uint4* __restrict__ kg = (const uint4*)p.k_suffix;
-    const uint4* __restrict__ vg = (const uint4*)p.v_suffix;
-    const int* __restrict__ pages = PAGED ? p.suffix_pages + p.suffix_page_indptr[n] : nullptr;
-    const int last_page = PAGED ? (Ls - 1) / 16 : 0;
-    constexpr int kRow = kD * 2 / 16;  // uint4 per KV row
-
-    // uint4 index of (token t of this sample, head j, 16-byte piece c)
-    auto row_index = [&](int t) -> long long {
-        if (PAGED) {
-            const long long pg = pages[min(t >> 4, last_page)];
-            return ((pg * p.Hkv + j) * 16 + (t & 15)) * kRow + c;
-        }
-        return (((long long)n * p.max_suffix_len + t) * p.Hkv + j) * kRow + c;
-    };
-
-    // Query fragments: B operand, column n = query head j*G + c (zero beyond G),
-    // k-slot (step s, lane-row r) = channels 32 s + 8 r .. + 7.
-    bf16x8 qf[4];
-    {
-        const uint4* qg = (const uint4*)p.q + ((long long)n * p.Hq + (long long)j * G + (c < G ? c : 0)) * kRow;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 v = qg[4 * s + r];
-            if (c >= G)
-                v = make_uint4(0, 0, 0, 0);
-            qf[s] = as_bf16x8(v);
-        }
-    }
-
-    uint4 kreg[8], vreg[8];
-    auto load_tile = [&](int tb, uint4 (&kk)[8], uint4 (&vv)[8]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int t = min(tb + tile_token(r, s), t1 - 1);
-            const long long idx = row_index(t);
-            kk[s] = kg[idx];
-            vv[s] = vg[idx];
-        }
-    };
-    auto stage_k = [&](const uint4 (&kk)[8]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-            ksm[wave][tile_token(r, s)][c] = kk[s];
-    };
-
-    float m_run = -INFINITY;  // running maximum of query head c (replicated over lane-rows)
-    float l_run = 0.f;        // this lane's share of the running sum
-    floatx4 o[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    load_tile(t0, kreg, vreg);
-    stage_k(kreg);
-
-    for (int tb = t0; tb < t1; tb += kTile) {
-        const bool more = tb + kTile < t1;
-        uint4 knext[8], vnext[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            knext[s] = make_uint4(0, 0, 0, 0);
-            vnext[s] = make_uint4(0, 0, 0, 0);
-        }
-        if (more)
-            load_tile(tb + kTile, knext, vnext);
-
-        // ---- S^T = K Q^T for the two 16-token blocks ---------------------------------------
-        floatx4 sacc[2];
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            sacc[blk] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 kf = as_bf16x8(ksm[wave][16 * blk + c][4 * s + r]);
-                sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], sacc[blk], 0, 0, 0);
-            }
-        }
-        // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c;
-        // scores stay unscaled, the scale is folded into the exponent: p = 2^(s * scale - m)
-        float sv[8];
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = tb + 16 * blk + 4 * r + i;
-                sv[4 * blk + i] = t < t1 ? sacc[blk][i] : -INFINITY;
-                tmax = fmaxf(tmax, sv[4 * blk + i]);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax * p.scale_log2);  // finite: the tile holds a valid token
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);  // 0 on the first tile
-        float psum = 0.f;
-        float pv[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[i], p.scale_log2, -m_new));
-            psum += pv[i];
-        }
-        l_run = l_run * corr + psum;
-        uint4 pu;
-        pu.x = pack_bf16_rne(pv[0], pv[1]);
-        pu.y = pack_bf16_rne(pv[2], pv[3]);
-        pu.z = pack_bf16_rne(pv[4], pv[5]);
-        pu.w = pack_bf16_rne(pv[6], pv[7]);
-        const bf16x8 pf = as_bf16x8(pu);
-
-        // ---- rescale the accumulator when some head's maximum moved ---------------------------
-        if (__ballot(m_new != m_run)) {
-            // accumulator register i of lane-row r belongs to query head 4 r + i
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float f = __shfl(corr, (4 * r + i) & 15);
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    o[k][i] *= f;
-            }
-        }
-        m_run = m_new;
-
-        // ---- O += P V: transpose V in registers, one MFMA per channel residue ------------------
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            uint4 f;
-            f.x = __builtin_amdgcn_perm(dword(vreg[1], i >> 1), dword(vreg[0], i >> 1), sel);
-            f.y = __builtin_amdgcn_perm(dword(vreg[3], i >> 1), dword(vreg[2], i >> 1), sel);
-            f.z = __builtin_amdgcn_perm(dword(vreg[5], i >> 1), dword(vreg[4], i >> 1), sel);
-            f.w = __builtin_amdgcn_perm(dword(vreg[7], i >> 1), dword(vreg[6], i >> 1), sel);
-            // column c of this MFMA is channel 8 c + i
-            o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, as_bf16x8(f), o[i], 0, 0, 0);
-        }
-
-        if (more) {
-            stage_k(knext);
-#pragma unroll
-            for (int s = 0; s < 8; ++s)
-                vreg[s] = vnext[s];
-        }
-    }
-
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-
-    // ---- write the partial state ----------------------------------------------------------------
-    const long long row0 = (long long)n * p.Hq + (long long)j * G;  // first of the G output rows
-    if (r == 0 && c < G)
-        p.part_ml[part_index(p, row0 + c, slot0 + chunk)] = make_float2(m_run, l_run);
-    // the chunk's own normalised output, fp16: accumulator register i of lane-row r belongs to
-    // query head 4 r + i, whose l sits in the lanes with c == 4 r + i
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int g = 4 * r + i;
-        const float lg = __shfl(l_run, g & 15);
-        if (g < G) {
-            const float inv_l = 1.f / lg;  // > 0: the chunk holds at least one token
-            __half* dst = (__half*)p.part_acc + part_index(p, row0 + g, slot0 + chunk) * kD + 8 * c;
-            uint4 v;
-            __half2 h2;
-            h2 = __floats2half2_rn(o[0][i] * inv_l, o[1][i] * inv_l);
-            v.x = *reinterpret_cast<const uint32_t*>(&h2);
-            h2 = __floats2half2_rn(o[2][i] * inv_l, o[3][i] * inv_l);
-            v.y = *reinterpret_cast<const uint32_t*>(&h2);
-            h2 = __floats2half2_rn(o[4][i] * inv_l, o[5][i] * inv_l);
-            v.z = *reinterpret_cast<const uint32_t*>(&h2);
-            h2 = __floats2half2_rn(o[6][i] * inv_l, o[7][i] * inv_l);
-            v.w = *reinterpret_cast<const uint32_t*>(&h2);
-            *reinterpret_cast<uint4*>(dst) = v;
-        }
-    }
+    suffix_body<PAGED>(p, slot0, (long long)blockIdx.x * kWavesPerBlock + wave, ksm[wave]);
 }
 
 }  // namespace

@@ -91,6 +91,8 @@ int prefix_mfma_block_rows(int rows);
 hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s);
 bool suffix_mfma_supported(const AttnParams& p);
 hipError_t launch_attn_suffix_mfma(const AttnParams& p, hipStream_t s);
+bool attn_fused_supported(const AttnParams& p);
+hipError_t launch_attn_fused(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
 size_t sampler_workspace_bytes(long long rows, long long vocab);
 hipError_t launch_sampler(const SamplerParams& p, void* workspace, hipStream_t s);

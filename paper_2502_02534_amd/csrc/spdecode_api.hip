@@ -219,15 +219,26 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
                                (stages & SPD_STAGE_SUFFIX) && !suffix_tiled, s);
     if (e != hipSuccess)
         return SPD_ELAUNCH;
-    if ((stages & SPD_STAGE_PREFIX) && prefix_tiled) {
-        e = spd::launch_attn_prefix_mfma(p, s);
+    const bool both = (stages & SPD_STAGE_PREFIX) && (stages & SPD_STAGE_SUFFIX);
+    bool fused = both && spd::attn_fused_supported(p);
+#ifdef SPD_TUNING
+    if (getenv("SPD_TUNE_NO_FUSED")) fused = false;
+#endif
+    if (fused) {
+        e = spd::launch_attn_fused(p, s);
         if (e != hipSuccess)
             return SPD_ELAUNCH;
-    }
-    if ((stages & SPD_STAGE_SUFFIX) && suffix_tiled) {
-        e = spd::launch_attn_suffix_mfma(p, s);
-        if (e != hipSuccess)
-            return SPD_ELAUNCH;
+    } else {
+        if ((stages & SPD_STAGE_PREFIX) && prefix_tiled) {
+            e = spd::launch_attn_prefix_mfma(p, s);
+            if (e != hipSuccess)
+                return SPD_ELAUNCH;
+        }
+        if ((stages & SPD_STAGE_SUFFIX) && suffix_tiled) {
+            e = spd::launch_attn_suffix_mfma(p, s);
+            if (e != hipSuccess)
+                return SPD_ELAUNCH;
+        }
     }
     if (stages & SPD_STAGE_MERGE) {
         e = spd::launch_attn_merge(p, s);
