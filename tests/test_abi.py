@@ -83,3 +83,24 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.sample_tokens(one, 0, 4, 100, 100, one, one, one, one, z, 0, z) == 3         # no workspace
     rc = lib.shared_prefix_decode_attn(ctypes.byref(d), *([one] * 12), 128, 128, one, z, one, 16, z)
     assert rc == 3                                                                            # workspace too small
+
+
+@pytest.mark.parametrize("samples,hq,hkv,max_prefix,max_suffix", [
+    (1, 8, 8, 1, 0), (4, 4, 1, 256, 32), (16, 32, 8, 2048, 256), (64, 32, 8, 8192, 1024),
+    (32, 64, 8, 16384, 512), (1024, 32, 8, 16384, 2048), (2, 32, 8, 1 << 20, 1 << 17), (8, 16, 16, 100, 7),
+])
+def test_plan_invariants(lib, samples, hq, hkv, max_prefix, max_suffix):
+    """The launch plan is host arithmetic: parts cover the lengths, are whole tiles, and stay
+    within what the merge kernel can take (64 prefix splits + 64 suffix chunks)."""
+    from paper_2502_02534_amd import binding as B
+    desc = B.make_desc(dtype=B.SPD_BF16, num_q_heads=hq, num_kv_heads=hkv, head_dim=128, num_prompts=1,
+                       num_samples=samples, max_samples_per_prompt=samples, page_size=0)
+    split, nsplit, chunk, nchunk = B.spd_attn_plan(desc, max_prefix, max_suffix)
+    assert split % 64 == 0 and split > 0 and 1 <= nsplit <= 64
+    assert split * nsplit >= max_prefix > split * (nsplit - 1)
+    assert chunk % 32 == 0 and chunk > 0 and nchunk <= 64
+    assert chunk * nchunk >= max_suffix
+    if max_suffix > 0:
+        assert max_suffix > chunk * (nchunk - 1)
+    ws = B.shared_prefix_decode_attn_workspace_size(desc, max_prefix, max_suffix)
+    assert ws >= (nsplit + nchunk) * samples * hq * (128 * 2 + 8)
