@@ -30,9 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # machine).  Keyed by (kernel, workload); anything not listed is reported as null.  The entry
 # must be dropped when the kernel changes.  Source: profiles/hbm_traffic_cfg3_pmc.txt
 TRAFFIC_BYTES = {
-    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95487.6 * 2.0 + 20031.5) * 1024),
-    ("prefix", "cfg3-bf16-p8192-n64"): int((18517.2 * 2.0 + 18433.6) * 1024),
-    ("suffix", "cfg3-bf16-p8192-n64"): int((76977.6 * 2.0 + 1593.0) * 1024),
+    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95067.1 * 2.0 + 10889.5) * 1024),
+    ("suffix", "cfg3-bf16-p8192-n64"): int((76978.0 * 2.0 + 1593.0) * 1024),
 }
 
 
@@ -135,10 +134,10 @@ def main() -> int:
 
     it = args.kernel_iters
     # A step runs the prefix and the suffix pass in one launch when the library's fused kernel takes
-    # the shape (bf16, head_dim 128, more than 128 query rows per KV head, group size <= 16); the
+    # the shape (bf16, head_dim 128, more than 64 query rows per KV head, group size <= 16); the
     # two passes are also timed as launches of their own for their separate rooflines.
     max_rows = int(max(first.sample_indptr[b + 1] - first.sample_indptr[b] for b in range(sp.num_prompts))) * sp.group
-    fused = sp.dtype == "bf16" and sp.head_dim == 128 and max_rows > 128 and sp.group <= 16 and suffix_bytes > 0
+    fused = sp.dtype == "bf16" and sp.head_dim == 128 and max_rows > 64 and sp.group <= 16 and suffix_bytes > 0
     us = {
         "attn_fused": time_stage(attn_stage(B.STAGE_PREFIX | B.STAGE_SUFFIX), it),
         "prefix": time_stage(attn_stage(B.STAGE_PREFIX), it),

@@ -2,13 +2,15 @@
 // a dense row tile against the shared prompt KV, so the prompt is read once per row
 // tile instead of once per sample.
 //
-// Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix).
+// Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix); WAVES is 2
+// or 4.
 // A query row is (sample, head in group); each wavefront owns 32 rows (one 32-wide column
 // block of the transposed products).
 //
 // Data movement.  K and V tiles of 64 tokens go from global memory straight into LDS
-// (global_load_lds_dwordx4, no registers in between), four tiles deep, so two tiles are in
-// flight while one is being used.  Both tiles are row-major [token][256 bytes] without
+// (global_load_lds_dwordx4, no registers in between), into a ring of K slots and a ring of V
+// slots, one or two tiles ahead of the tile in use (K of a tile is needed one iteration before
+// its V).  Both tiles are row-major [token][256 bytes] without
 // padding; bank conflicts are avoided by an XOR swizzle of the 16-byte pieces of a row,
 // applied on the global side of the copy (lane L of a copy instruction always lands at
 // LDS offset 16 L, but it may fetch any piece).
@@ -45,9 +47,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;
 constexpr int kTileN = 64;               // tokens per tile
-constexpr int kStages = 4;               // LDS ring depth
 constexpr int kTileBytes = kTileN * 256;  // one K or V tile
-constexpr int kStageBytes = 2 * kTileBytes;
 constexpr int kRowU4 = kD * 2 / 16;
 constexpr int kAhead = 4;                // LDS fragments in flight ahead of the MFMAs
 
@@ -104,13 +104,19 @@ __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int,
     (f(std::integral_constant<int, I>{}), ...);
 }
 
-constexpr int kLdsBytes = kStages * kStageBytes;
+// LDS of a workgroup: KS slots for K tiles followed by VS slots for V tiles.
+constexpr int prefix_lds_bytes(int KS, int VS) { return (KS + VS) * kTileBytes; }
 
 // Body of one workgroup of WAVES wavefronts: (split, rowtile, z = prompt * Hkv + KV head).  `lds` is
-// kLdsBytes of LDS; every wavefront of the workgroup must call it (it uses workgroup barriers).
-template <int WAVES, bool PAGED>
+// prefix_lds_bytes(KS, VS) of LDS; every wavefront of the workgroup must call it (it uses
+// workgroup barriers).  Copies run AHEAD tiles ahead of the tile in use.  K of tile t is read
+// in iteration t and V of tile t in iteration t + 1, and the copies of tile t + AHEAD start at
+// the top of iteration t, so the rings need KS >= AHEAD + 1 and VS >= AHEAD + 2 slots.
+template <int WAVES, bool PAGED, int KS = 4, int VS = 4, int AHEAD = 2>
 __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int split, int rowtile, int z)
 {
+    static_assert(AHEAD == 1 || AHEAD == 2, "copy distance");
+    static_assert(KS >= AHEAD + 1 && VS >= AHEAD + 2, "rings too short for the copy distance");
     constexpr int kIPW = 32 / WAVES;  // copy instructions per wave per tile
 
     const int tid = threadIdx.x;
@@ -182,7 +188,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     fetch_pages(0);
     auto issue_tile = [&](int tile) __attribute__((always_inline)) {
         const int tb = t0 + tile * kTileN;
-        const int stage = tile % kStages;
+        const int kslot_bytes = (tile % KS) * kTileBytes, vslot_bytes = (KS + tile % VS) * kTileBytes;
         const bool full = tb + kTileN <= t1;
 #pragma unroll
         for (int i = 0; i < kIPW; ++i) {
@@ -200,7 +206,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
                 off = (unsigned)(rr * (unsigned)tok_stride + (((lane & 15) ^ swz(g + lane_row)) << 4));
             }
             const char* src = (q < 16 ? kg : vg) + base + off;
-            uint4* dst = lds + (stage * kStageBytes + (q >> 4) * kTileBytes + (q & 15) * 1024) / 16;
+            uint4* dst = lds + ((q < 16 ? kslot_bytes : vslot_bytes) + (q & 15) * 1024) / 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
         }
@@ -230,7 +236,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
             for (int part = 0; part < 2; ++part) {
                 const int tok = 8 * part + 4 * h + r;
                 const int piece = 4 * db + 2 * g16 + (q4 >> 1);
-                v_off[db][part] = (unsigned)(kTileBytes + tok * 256 + ((piece ^ swz(tok)) << 4) + (q4 & 1) * 8);
+                v_off[db][part] = (unsigned)(tok * 256 + ((piece ^ swz(tok)) << 4) + (q4 & 1) * 8);
             }
     }
 
@@ -254,8 +260,8 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     auto region = [&](auto qk_tag, auto pv_tag, int kstage, int vstage) __attribute__((always_inline)) {
         constexpr bool QK = decltype(qk_tag)::value, PV = decltype(pv_tag)::value;
         constexpr int NF = frag_count<QK, PV>();
-        const unsigned kbase = lds_base + kstage * kStageBytes;
-        const unsigned vbase = lds_base + vstage * kStageBytes;
+        const unsigned kbase = lds_base + (unsigned)kstage * kTileBytes;
+        const unsigned vbase = lds_base + (unsigned)(KS + vstage) * kTileBytes;
         if (QK) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -364,16 +370,16 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     };
 
     // ---- pipeline over tiles ----------------------------------------------------------------------
-    // Iteration `it` starts the copies of tile it+2, runs one MFMA region (scores of tile `it`
+    // Iteration `it` starts the copies of tile it+AHEAD, runs one MFMA region (scores of tile `it`
     // together with P V of tile it-1), waits until its own copies of tile it+1 have landed, meets
     // the other wavefronts at a barrier, then runs the softmax of tile `it`.
     const int ntiles = (t1 - t0 + kTileN - 1) / kTileN;
     const std::true_type yes{};
     const std::false_type no{};
     issue_tile(0);
-    if (ntiles > 1)
+    if (AHEAD == 2 && ntiles > 1)
         issue_tile(1);
-    if (ntiles > 1)
+    if (AHEAD == 2 && ntiles > 1)
         wait_vmcnt<kIPW>();
     else
         wait_vmcnt<0>();
@@ -384,7 +390,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     // wavefront reaches after its copies of that tile landed.
     auto end_of_region = [&](int it) __attribute__((always_inline)) {
         if (it + 1 < ntiles) {
-            if (it + 2 < ntiles)
+            if (AHEAD == 2 && it + 2 < ntiles)
                 wait_vmcnt<kIPW>();
             else
                 wait_vmcnt<0>();
@@ -392,19 +398,19 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
         }
     };
     // first tile: scores only (kept out of the loop so that the loop body is one straight path)
-    if (ntiles > 2)
-        issue_tile(2);
+    if (ntiles > AHEAD)
+        issue_tile(AHEAD);
     region(yes, no, 0, 0);
     end_of_region(0);
     softmax_tile(t0);
     for (int it = 1; it < ntiles; ++it) {
-        if (it + 2 < ntiles)
-            issue_tile(it + 2);
-        region(yes, yes, it % kStages, (it - 1) % kStages);
+        if (it + AHEAD < ntiles)
+            issue_tile(it + AHEAD);
+        region(yes, yes, it % KS, (it - 1) % VS);
         end_of_region(it);
         softmax_tile(t0 + it * kTileN);
     }
-    region(no, yes, 0, (ntiles - 1) % kStages);
+    region(no, yes, 0, (ntiles - 1) % VS);
 
     // ---- write the partial state ------------------------------------------------------------------
     const float l = l_run + __shfl_xor(l_run, 32);

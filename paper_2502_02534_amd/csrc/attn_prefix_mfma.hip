@@ -6,11 +6,15 @@ namespace {
 
 using namespace prefix_impl;
 
+// 128-row workgroups (4 wavefronts) take the short rings (80 KB) so that two of them share a CU;
+// 64-row workgroups (2 wavefronts) keep the long rings, copies two tiles ahead.
 template <int WAVES, bool PAGED>
-__global__ __launch_bounds__(WAVES * 64) void attn_prefix_mfma_kernel(AttnParams p)
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES == 4 ? 2 : 1, 2))) void
+attn_prefix_mfma_kernel(AttnParams p)
 {
-    __shared__ uint4 lds[kLdsBytes / 16];
-    prefix_body<WAVES, PAGED>(p, lds, blockIdx.x, blockIdx.y, blockIdx.z);
+    constexpr int KS = WAVES == 4 ? 2 : 4, VS = WAVES == 4 ? 3 : 4, AHEAD = WAVES == 4 ? 1 : 2;
+    __shared__ uint4 lds[prefix_lds_bytes(KS, VS) / 16];
+    prefix_body<WAVES, PAGED, KS, VS, AHEAD>(p, lds, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 template <int WAVES>
@@ -34,22 +38,22 @@ bool prefix_mfma_supported(const AttnParams& p)
            (p.page_size == 0 || p.page_size == 16) && (long long)p.B * p.Hkv <= 65535;
 }
 
-// Rows per workgroup used for a problem with `rows` query rows per (prompt, KV head):
-// 32 rows per wavefront, 2 to 8 wavefronts.
+// Rows per workgroup that the split plan and the fused launch assume for a problem with `rows` query
+// rows per (prompt, KV head): 32 rows per wavefront, 2 or 4 wavefronts.  (Workgroups of 8 wavefronts
+// and 256 rows are slower as soon as the pass shares a launch with the suffix pass: a 4-wavefront
+// workgroup leaves room on its CU for a suffix workgroup.)
 int prefix_mfma_block_rows(int rows)
 {
-    return rows > 128 ? 256 : rows > 64 ? 128 : 64;
+    return rows > 64 ? 128 : 64;
 }
 
 hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s)
 {
     if (p.num_prefix_splits <= 0)
         return hipSuccess;
-    switch (prefix_mfma_block_rows(p.max_spp * p.G)) {
-    case 256: return launch_waves<8>(p, s);
-    case 128: return launch_waves<4>(p, s);
-    default: return launch_waves<2>(p, s);
-    }
+    if (prefix_mfma_block_rows(p.max_spp * p.G) == 128)
+        return launch_waves<4>(p, s);
+    return launch_waves<2>(p, s);
 }
 
 }  // namespace spd
