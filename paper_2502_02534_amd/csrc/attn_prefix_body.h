@@ -186,10 +186,30 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
         }
     };
     fetch_pages(0);
+    // Contiguous KV, whole tiles: the source of copy i is a fixed pointer (tensor, KV head, first row
+    // of the group) plus a per-tile offset shared by all copies, so a copy costs one 64-bit add.
+    const char* group_ptr[kIPW];
+#pragma unroll
+    for (int i = 0; i < kIPW; ++i) {
+        const int q = wave * kIPW + i;
+        group_ptr[i] = (q < 16 ? kg : vg) + head_base + (long long)(4 * (q & 15)) * tok_stride;
+    }
     auto issue_tile = [&](int tile) __attribute__((always_inline)) {
         const int tb = t0 + tile * kTileN;
         const int kslot_bytes = (tile % KS) * kTileBytes, vslot_bytes = (KS + tile % VS) * kTileBytes;
         const bool full = tb + kTileN <= t1;
+        if (!PAGED && full) {
+            const long long tile_off = (long long)tb * tok_stride;
+#pragma unroll
+            for (int i = 0; i < kIPW; ++i) {
+                const int q = wave * kIPW + i;
+                const char* src = group_ptr[i] + tile_off + lane_off[i];
+                uint4* dst = lds + ((q < 16 ? kslot_bytes : vslot_bytes) + (q & 15) * 1024) / 16;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < kIPW; ++i) {
             const int q = wave * kIPW + i;
