@@ -100,6 +100,16 @@ RAGGED = [
          prefix_len=(1, 500), suffix_len=(0, 200), page_size=16),
     dict(dtype="bf16", num_q_heads=4, num_kv_heads=4, head_dim=128, num_prompts=2, samples_per_prompt=33,
          prefix_len=(100, 200), suffix_len=(0, 40), page_size=16),
+    # more than 64 query rows per KV head: prefix and suffix pass share one launch (128-row tiles;
+    # 80 rows = one partial tile, 160 rows = one full + one partial, 264 rows = three tiles)
+    dict(dtype="bf16", num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=3, samples_per_prompt=20,
+         prefix_len=(1, 700), suffix_len=(0, 300)),
+    dict(dtype="bf16", num_q_heads=16, num_kv_heads=4, head_dim=128, num_prompts=2, samples_per_prompt=40,
+         prefix_len=(63, 1100), suffix_len=(0, 400), page_size=16),
+    dict(dtype="bf16", num_q_heads=8, num_kv_heads=1, head_dim=128, num_prompts=2, samples_per_prompt=33,
+         prefix_len=(64, 129), suffix_len=(1, 33)),
+    dict(dtype="bf16", num_q_heads=16, num_kv_heads=2, head_dim=128, num_prompts=1, samples_per_prompt=24,
+         prefix_len=(2049, 2049), suffix_len=(0, 0)),
 ]
 
 
@@ -163,6 +173,17 @@ def test_sampler_strided_rows(dev, oracle, vocab, row_stride):
     the whole-row kernel; the padding columns hold 1e30 and must never be read as logits."""
     print(f"sampler strided vocab {vocab} stride {row_stride}", flush=True)
     check_tokens(dev, oracle, _sampler_case(24, vocab, 3, 0.8, 0.9, 900 + row_stride), row_stride=row_stride)
+
+
+def test_temperature_sweep_in_one_batch(dev, oracle):
+    """The paper samples 64 completions at each of three temperatures from one prompt (App.,
+    experiment settings): 192 samples share the prefix, the temperature is per sample."""
+    print("temperature sweep batch", flush=True)
+    spec = W.small_spec(dtype="bf16", num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1,
+                        samples_per_prompt=192, prefix_len=(3000, 3000), suffix_len=(1, 600))
+    check_attention(dev, oracle, W.make_attn_inputs(0, spec=spec, seed=4242, poison_padding=True))
+    T = np.repeat(np.asarray([0.4, 0.7, 1.0], np.float32), 64)
+    check_tokens(dev, oracle, _sampler_case(192, 32000, 3, T, 0.95, 4243))
 
 
 def test_sampler_mixed_per_row_parameters(dev, oracle):
