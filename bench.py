@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=50)
+    ap.add_argument("--loop-steps", type=int, default=48,
+                    help="decode steps of the append + attention + sampler loop timed eagerly and as a "
+                         "replayed graph (0 = skip; single-layer workloads only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -187,6 +190,64 @@ def main() -> int:
                     "unit": "GB/s", "frac": kernels[dom]["frac_hbm_peak"],
                     "traffic": TRAFFIC_BYTES.get((dom, sp.name))}
 
+    # ---- loop of decode steps with KV append (device-side lengths), eager and as a replayed graph ----
+    loop_info = None
+    if args.loop_steps > 0 and sp.layers == 1:
+        L = args.loop_steps
+        host = layers_host[0]
+        import copy as _copy
+        hl = _copy.copy(host)
+        hl.suffix_lens = np.maximum(host.suffix_lens - L - 1, 0).astype(np.int32)  # room for the steps
+        rng = np.random.default_rng(12345)
+        n = sp.num_samples
+
+        def draw(shape):
+            x = rng.standard_normal(shape).astype(np.float32)
+            t = torch.from_numpy(workloads.f32_to_bf16_bits(x) if sp.dtype == "bf16" else x).cuda()
+            return t.view(torch.int16).view(torch.bfloat16) if sp.dtype == "bf16" else t
+
+        q_s = draw((L, n, sp.num_q_heads, sp.head_dim))
+        k_s = draw((L, n, sp.num_kv_heads, sp.head_dim))
+        v_s = draw((L, n, sp.num_kv_heads, sp.head_dim))
+        u_s = torch.from_numpy(rng.random((L, sin.logits.shape[0]), dtype=np.float32)).cuda()
+
+        def make_loop():
+            return device.DecodeLoop(device.upload_attn(hl), device.upload_sampler(sin), q_s, k_s, v_s, u_s, -1)
+
+        lp = make_loop()
+        lp.one_step()
+        lp.step.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(L - 1):
+            lp.one_step()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) / (L - 1) * 1e6
+        gl = make_loop()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            gl.one_step()
+        torch.cuda.current_stream().wait_stream(side)
+        gl.step.zero_()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            gl.one_step()
+        graph.replay()
+        gl.step.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(L - 2):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / (L - 2) * 1e6
+        loop_info = {"steps": L, "us_per_step_eager": eager_us, "us_per_step_graph": graph_us,
+                     "tokens_per_sec_graph": sp.num_samples * 1e6 / graph_us,
+                     "note": "append_suffix_kv + attention + sample_tokens per step, per-step inputs gathered "
+                             "on the device, lengths on the device; graph = one captured step replayed"}
+        del lp, gl, graph, q_s, k_s, v_s, u_s
+
     if args.calibrate_copy:
         # a plain elementwise kernel of known size in the same process: 256 MiB read and 256 MiB
         # written per call (torch's out-of-place multiply; a tensor copy would go to the runtime's
@@ -234,7 +295,7 @@ def main() -> int:
         "tokens_per_sec": sp.num_samples * 1e3 / ms_per_step,
         "step_algorithmic_bytes": step_bytes,
         "step_GBps": step_bytes / ms_per_step / 1e6,
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "decode_loop": loop_info, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     return 0

@@ -163,6 +163,38 @@ SPD_API int sample_tokens(const void *logits, int32_t logits_dtype,
                   void *workspace, size_t workspace_bytes,
                   void *stream);
 
+/*
+ * Between two decode steps of the sampling loop (the paper generates up to 1024
+ * tokens per sample, App. "Experiment settings"): append one token's K and V to the
+ * private suffix of every live sample and add one to its suffix_lens entry, all on
+ * the device, so that a loop of decode steps needs no host synchronisation.
+ *
+ *   desc              dtype, num_kv_heads, head_dim, num_samples, page_size as for the
+ *                     attention call (the other fields are ignored)
+ *   k_new, v_new      [N, Hkv, D], desc->dtype: the new token of each sample
+ *   k_suffix/v_suffix, suffix_page_indptr, suffix_page_indices: as for the attention
+ *                     call (written here)
+ *   suffix_lens       int32 [N], read and incremented
+ *   max_suffix_len    capacity of a sample's slot in tokens (contiguous: the slot stride;
+ *                     paged: 16 * pages in the sample's page list).  A full sample is
+ *                     left unchanged.
+ *   last_tokens       int32 [N] or NULL: the token each sample drew in the previous step
+ *   end_token         a sample whose last token equals it is marked finished
+ *   finished          int32 [N] or NULL (then no sample ever finishes); nonzero = finished.
+ *                     Finished samples are left unchanged; the flags persist across calls.
+ *
+ * All pointers are device pointers, 16-byte aligned.  Returns spd_status.
+ */
+SPD_API int append_suffix_kv(const spd_attn_desc *desc,
+                     const void *k_new, const void *v_new,
+                     void *k_suffix, void *v_suffix,
+                     int32_t *suffix_lens,
+                     const int32_t *suffix_page_indptr,
+                     const int32_t *suffix_page_indices,
+                     int64_t max_suffix_len,
+                     const int32_t *last_tokens, int32_t end_token, int32_t *finished,
+                     void *stream);
+
 /* Short description of a status code (static storage). */
 SPD_API const char *spd_status_string(int status);
 

@@ -60,6 +60,8 @@ def load() -> ctypes.CDLL:
     lib.sample_tokens_workspace_size.argtypes = [i64, i64]
     lib.sample_tokens.restype = ctypes.c_int
     lib.sample_tokens.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.append_suffix_kv.restype = ctypes.c_int
+    lib.append_suffix_kv.argtypes = [dp] + [vp] * 7 + [i64, vp, ctypes.c_int32, vp, vp]
     _lib = lib
     return lib
 
@@ -124,3 +126,14 @@ def sample_tokens(logits, logits_dtype: int, rows: int, vocab: int, row_stride: 
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "sample_tokens")
+
+
+def append_suffix_kv(desc: AttnDesc, k_new, v_new, k_suffix, v_suffix, suffix_lens, suffix_page_indptr,
+                     suffix_page_indices, max_suffix_len: int, last_tokens=None, end_token: int = -1,
+                     finished=None, stream=None) -> None:
+    rc = load().append_suffix_kv(
+        ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _ptr(k_suffix), _ptr(v_suffix), _ptr(suffix_lens),
+        _ptr(suffix_page_indptr), _ptr(suffix_page_indices), int(max_suffix_len), _ptr(last_tokens),
+        int(end_token), _ptr(finished), _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "append_suffix_kv")

@@ -44,6 +44,21 @@ struct AttnParams {
     float* lse;
 };
 
+struct KvAppendParams {
+    int N, Hkv, D, elt, page_size;
+    int capacity;             // tokens a sample's slot (or page list) can hold
+    const void* k_new;        // [N, Hkv, D]
+    const void* v_new;
+    void* k_suffix;
+    void* v_suffix;
+    int* suffix_lens;
+    const int* page_indptr;
+    const int* pages;
+    const int* last_tokens;   // may be null
+    int end_token;
+    int* finished;            // may be null
+};
+
 struct SamplerParams {
     const float* logits;
     long long rows, vocab, stride;
@@ -94,6 +109,7 @@ hipError_t launch_attn_suffix_mfma(const AttnParams& p, hipStream_t s);
 bool attn_fused_supported(const AttnParams& p);
 hipError_t launch_attn_fused(const AttnParams& p, hipStream_t s);
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
+hipError_t launch_kv_append(const KvAppendParams& a, hipStream_t s);
 size_t sampler_workspace_bytes(long long rows, long long vocab);
 hipError_t launch_sampler(const SamplerParams& p, void* workspace, hipStream_t s);
 

@@ -108,6 +108,45 @@ inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0
 
 extern "C" {
 
+int append_suffix_kv(const spd_attn_desc* desc, const void* k_new, const void* v_new, void* k_suffix,
+                     void* v_suffix, int32_t* suffix_lens, const int32_t* suffix_page_indptr,
+                     const int32_t* suffix_page_indices, int64_t max_suffix_len, const int32_t* last_tokens,
+                     int32_t end_token, int32_t* finished, void* stream)
+{
+    if (!desc)
+        return SPD_EINVAL;
+    const int rc = check_desc(desc);
+    if (rc != SPD_OK)
+        return rc;
+    if (!k_new || !v_new || !k_suffix || !v_suffix || !suffix_lens)
+        return SPD_EINVAL;
+    if (desc->page_size != 0 && (!suffix_page_indptr || !suffix_page_indices))
+        return SPD_EINVAL;
+    if (max_suffix_len < 0 || max_suffix_len > (1ll << 30))
+        return SPD_EINVAL;
+    const int elt = desc->dtype == SPD_BF16 ? 2 : 4;
+    if ((desc->head_dim * elt) % 16 != 0)
+        return SPD_EUNSUPPORTED;
+    spd::KvAppendParams a;
+    a.N = desc->num_samples;
+    a.Hkv = desc->num_kv_heads;
+    a.D = desc->head_dim;
+    a.elt = elt;
+    a.page_size = desc->page_size;
+    a.capacity = (int)max_suffix_len;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.k_suffix = k_suffix;
+    a.v_suffix = v_suffix;
+    a.suffix_lens = suffix_lens;
+    a.page_indptr = suffix_page_indptr;
+    a.pages = suffix_page_indices;
+    a.last_tokens = last_tokens;
+    a.end_token = end_token;
+    a.finished = finished;
+    return spd::launch_kv_append(a, (hipStream_t)stream) == hipSuccess ? SPD_OK : SPD_ELAUNCH;
+}
+
 const char* spd_status_string(int status)
 {
     switch (status) {

@@ -106,3 +106,50 @@ def upload_sampler(inp, device="cuda:0", row_stride=None, pad_value=float("nan")
         logits = _dev(inp.logits, device)
     return DeviceSampler(logits, _dev(inp.temperature, device), _dev(inp.top_p, device),
                          _dev(inp.uniforms, device), torch.empty(rows, dtype=torch.int32, device=device), ws)
+
+
+class DecodeLoop:
+    """A loop of decode steps on the device: append the step's K/V (synthetic: there are no
+    weights), attention, sampling; lengths, finished flags and the step counter live on the
+    device, so the steps can be replayed from a captured graph without host synchronisation.
+
+    Per-step inputs are rows of tensors indexed by a device-side step counter:
+      q_steps [steps, N, Hq, D], k_steps / v_steps [steps, N, Hkv, D], u_steps [steps, rows].
+    The logits are the same every step (only the uniforms change); `tokens_steps` and `out_steps`
+    record every step's results for checking."""
+
+    def __init__(self, attn: DeviceAttn, sampler: DeviceSampler, q_steps, k_steps, v_steps, u_steps,
+                 end_token: int = -1):
+        self.attn, self.sampler = attn, sampler
+        self.q_steps, self.k_steps, self.v_steps, self.u_steps = q_steps, k_steps, v_steps, u_steps
+        self.steps = q_steps.shape[0]
+        dev = q_steps.device
+        n = attn.q.shape[0]
+        self.step = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.finished = torch.zeros(n, dtype=torch.int32, device=dev)
+        self.end_token = end_token
+        sampler.tokens.fill_(-1)  # "no token yet": never equal to an end token (>= 0)
+        self.k_cur = torch.empty_like(k_steps[0])
+        self.v_cur = torch.empty_like(v_steps[0])
+        self.tokens_steps = torch.full((self.steps, sampler.tokens.shape[0]), -1, dtype=torch.int32, device=dev)
+        self.out_steps = torch.zeros((self.steps,) + tuple(attn.out.shape), dtype=attn.out.dtype, device=dev)
+        self.lens_steps = torch.zeros((self.steps, n), dtype=torch.int32, device=dev)
+
+    def one_step(self) -> None:
+        """Enqueues one decode step on the current stream (capturable: no allocation that the
+        caching allocator cannot replay, no synchronisation)."""
+        a, s = self.attn, self.sampler
+        idx = self.step  # device-side counter
+        a.q.copy_(self.q_steps.index_select(0, idx)[0])
+        self.k_cur.copy_(self.k_steps.index_select(0, idx)[0])
+        self.v_cur.copy_(self.v_steps.index_select(0, idx)[0])
+        s.uniforms.copy_(self.u_steps.index_select(0, idx)[0])
+        B.append_suffix_kv(a.desc, self.k_cur, self.v_cur, a.k_suffix, a.v_suffix, a.suffix_lens,
+                           a.suffix_page_indptr, a.suffix_page_indices, a.max_suffix_len,
+                           s.tokens, self.end_token, self.finished)
+        a.run()
+        s.run()
+        self.tokens_steps.index_copy_(0, idx, s.tokens.unsqueeze(0))
+        self.out_steps.index_copy_(0, idx, a.out.unsqueeze(0))
+        self.lens_steps.index_copy_(0, idx, a.suffix_lens.unsqueeze(0))
+        self.step.add_(1)

@@ -1,0 +1,158 @@
+"""Loop of decode steps with KV append on the device (`append_suffix_kv` + attention + sampler),
+checked step by step against the CPU checker run on the same growing KV; then the same loop
+replayed from a captured graph must reproduce the eager results bit for bit."""
+import copy
+
+import numpy as np
+import pytest
+
+from paper_2502_02534_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+STEPS = 9
+VOCAB = 4099
+CASES = [
+    dict(dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=2, samples_per_prompt=6,
+         prefix_len=(40, 300), suffix_len=(0, 60)),
+    dict(dtype="bf16", num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1, samples_per_prompt=24,
+         prefix_len=(700, 700), suffix_len=(0, 90)),
+    dict(dtype="bf16", num_q_heads=16, num_kv_heads=4, head_dim=128, num_prompts=2, samples_per_prompt=20,
+         prefix_len=(100, 500), suffix_len=(0, 70), page_size=16),
+    dict(dtype="f32", num_q_heads=4, num_kv_heads=2, head_dim=64, num_prompts=1, samples_per_prompt=5,
+         prefix_len=(33, 33), suffix_len=(0, 20)),
+]
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2502_02534_amd import binding, device
+    binding.load()
+    return device
+
+
+def _step_inputs(inp, seed):
+    sp = inp.spec
+    rng = np.random.default_rng(seed)
+    n = inp.q.shape[0]
+    def draw(shape):
+        x = rng.standard_normal(shape).astype(np.float32)
+        return W.f32_to_bf16_bits(x) if sp.dtype == "bf16" else x
+    q = draw((STEPS, n, sp.num_q_heads, sp.head_dim))
+    k = draw((STEPS, n, sp.num_kv_heads, sp.head_dim))
+    v = draw((STEPS, n, sp.num_kv_heads, sp.head_dim))
+    u = rng.random((STEPS, n), dtype=np.float32)
+    logits = (rng.standard_normal((n, VOCAB)) * 3).astype(np.float32)
+    return q, k, v, u, logits
+
+
+def _capacity(inp):
+    n = inp.q.shape[0]
+    if inp.spec.page_size == 0:
+        return np.full(n, inp.max_suffix_len, dtype=np.int64)
+    pages = np.diff(inp.suffix_page_indptr).astype(np.int64)
+    return np.minimum(pages * inp.spec.page_size, inp.max_suffix_len)
+
+
+def _host_append(inp, n, pos, krow, vrow):
+    if inp.spec.page_size == 0:
+        inp.k_suffix[n, pos] = krow
+        inp.v_suffix[n, pos] = vrow
+    else:
+        P = inp.spec.page_size
+        pg = inp.suffix_page_indices[inp.suffix_page_indptr[n] + pos // P]
+        inp.k_suffix[pg, :, pos % P, :] = krow
+        inp.v_suffix[pg, :, pos % P, :] = vrow
+
+
+@pytest.mark.parametrize("i", range(len(CASES)))
+def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i):
+    print(f"decode loop case {i}: {CASES[i]}", flush=True)
+    inp = W.make_attn_inputs(0, spec=W.small_spec(**CASES[i]), seed=700 + i)
+    # leave every sample room for the steps inside its own slot / page list where it had any
+    inp.suffix_lens = np.maximum(inp.suffix_lens - STEPS + 2, 0).astype(np.int32)
+    q, k, v, u, logits = _step_inputs(inp, 800 + i)
+    n = inp.q.shape[0]
+    temp = np.full(n, 0.8, np.float32)
+    top_p = np.full(n, 0.9, np.float32)
+    bf16 = inp.spec.dtype == "bf16"
+
+    # ---- checker: the same loop on the host ----
+    tokens_ref = [oracle.sample_tokens(logits, temp, top_p, u[t]) for t in range(STEPS)]
+    end_token = int(np.bincount(tokens_ref[1]["token"]).argmax())  # some samples finish after step 1
+    host = copy.deepcopy(inp)
+    cap = _capacity(host)
+    finished = np.zeros(n, dtype=bool)
+    ref_out, ref_lens = [], []
+    for t in range(STEPS):
+        if t > 0:
+            finished |= tokens_ref[t - 1]["token"] == end_token
+        for s in range(n):
+            pos = int(host.suffix_lens[s])
+            if not finished[s] and pos < cap[s]:
+                _host_append(host, s, pos, k[t, s], v[t, s])
+                host.suffix_lens[s] = pos + 1
+        host.q = q[t]
+        out, _ = oracle.attention_inputs(host)
+        ref_out.append(out)
+        ref_lens.append(host.suffix_lens.copy())
+    assert finished.any() and not finished.all()
+
+    # ---- device: eager loop ----
+    def fresh_loop():
+        a = dev.upload_attn(inp)
+        s = dev.upload_sampler(W.SamplerInputs(logits, temp, top_p, u[0].copy()))
+        to = lambda x: torch.from_numpy(x).cuda()
+        as_el = (lambda x: to(x).view(torch.int16).view(torch.bfloat16)) if bf16 else to
+        return dev.DecodeLoop(a, s, as_el(q), as_el(k), as_el(v), to(u), end_token)
+
+    loop = fresh_loop()
+    for t in range(STEPS):
+        loop.one_step()
+    torch.cuda.synchronize()
+    lens = loop.lens_steps.cpu().numpy()
+    toks = loop.tokens_steps.cpu().numpy()
+    outs = loop.out_steps.float().cpu().numpy().astype(np.float64)
+    for t in range(STEPS):
+        assert np.array_equal(lens[t], ref_lens[t]), (t, lens[t], ref_lens[t])
+        err = np.abs(outs[t] - ref_out[t])
+        if bf16:
+            assert err.max() <= 2e-2, (t, err.max())
+        else:
+            assert np.all(err <= 1e-5 * np.abs(ref_out[t]) + 1e-6), (t, err.max())
+        o = tokens_ref[t]
+        uu = u[t].astype(np.float64)
+        near = (np.minimum(np.abs(uu - o["cdf_lo"]), np.abs(uu - o["cdf_hi"])) < 1e-6) | (o["cut_margin"] < 1e-6)
+        assert np.all((toks[t] == o["token"]) | near), (t, toks[t], o["token"])
+
+    # ---- device: one step captured as a graph, replayed STEPS times ----
+    g_loop = fresh_loop()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g_loop.one_step()          # warm-up outside the capture (same stream rules as a capture)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # restore the state the warm-up step changed
+    fresh = fresh_loop()
+    g_loop.attn.k_suffix.copy_(fresh.attn.k_suffix)
+    g_loop.attn.v_suffix.copy_(fresh.attn.v_suffix)
+    g_loop.attn.suffix_lens.copy_(fresh.attn.suffix_lens)
+    g_loop.finished.zero_()
+    g_loop.step.zero_()
+    g_loop.sampler.tokens.fill_(-1)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g_loop.one_step()
+    # the capture itself executes nothing; replay the step STEPS times with eager work in between
+    for t in range(STEPS):
+        graph.replay()
+        _ = (g_loop.attn.out.float().sum() + t).item()   # eager kernel + host synchronisation between replays
+    torch.cuda.synchronize()
+    assert torch.equal(g_loop.lens_steps, loop.lens_steps)
+    assert torch.equal(g_loop.tokens_steps, loop.tokens_steps)
+    assert torch.equal(g_loop.out_steps.view(torch.uint8), loop.out_steps.view(torch.uint8))
