@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
         const long long item = (long long)(blk - prefix_blocks) * kFusedWaves + wave;
         typedef uint4 (*wave_tile_t)[suffix_impl::kRowU4];
         suffix_impl::suffix_body<PAGED>(
-            p, p.num_prefix_splits, item,
+            p, p.suffix_slot0, item,
             (wave_tile_t)((char*)lds + (size_t)wave * suffix_impl::kWaveLdsBytes));
     }
 }

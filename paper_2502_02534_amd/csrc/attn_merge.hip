@@ -63,18 +63,39 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
     const long long row = (long long)blockIdx.x * rows_per_block + r_in;
     const bool row_ok = row < total;
 
-    int np = 0, ns = 0;
+    // valid partials of the row: the splits of every prefix level that lie inside the group's
+    // length, then the suffix chunks inside the sample's length; cum[l] counts those before level l
+    int cum[kMaxLevels + 1];
+    int ns = 0;
+#pragma unroll
+    for (int l = 0; l <= kMaxLevels; ++l)
+        cum[l] = 0;
     if (row_ok) {
         const int n = (int)(row / p.Hq);
-        const int b = prompt_of_sample(p.sample_indptr, p.B, n);
-        const int Lp = p.prefix_lens[b], Ls = p.suffix_lens[n];
-        np = p.prefix_split_tokens > 0 ? (Lp + p.prefix_split_tokens - 1) / p.prefix_split_tokens : 0;
+#pragma unroll
+        for (int l = 0; l < kMaxLevels; ++l) {
+            int c = 0;
+            if (l < p.num_levels && p.mlev[l].split_tokens > 0) {
+                const int b = prompt_of_sample(p.mlev[l].sample_indptr, p.mlev[l].B, n);
+                c = (p.mlev[l].lens[b] + p.mlev[l].split_tokens - 1) / p.mlev[l].split_tokens;
+            }
+            cum[l + 1] = cum[l] + c;
+        }
+        const int Ls = p.suffix_lens[n];
         ns = p.suffix_chunk_tokens > 0 ? (Ls + p.suffix_chunk_tokens - 1) / p.suffix_chunk_tokens : 0;
     }
+    const int np = cum[kMaxLevels];
     const int cnt = np + ns;
     const bool ch_ok = row_ok && 4 * c < p.D;
     const elem_t* base = (const elem_t*)p.part_acc + part_index(p, row_ok ? row : 0, 0) * p.D + 4 * c;
-    auto slot_at = [&](int i) { return i < np ? i : p.num_prefix_splits + (i - np); };
+    auto slot_at = [&](int i) {
+        int slot = p.suffix_slot0 + (i - np);
+#pragma unroll
+        for (int l = kMaxLevels - 1; l >= 0; --l)
+            if (i < cum[l + 1])
+                slot = p.mlev[l].slot0 + (i - cum[l]);
+        return slot;
+    };
     // The first batch of accumulator loads does not need the weights: it is issued together
     // with the (m, l) loads so that both round trips overlap.
     constexpr int kBatch = 32;

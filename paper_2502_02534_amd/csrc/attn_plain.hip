@@ -133,16 +133,16 @@ hipError_t launch_attn_plain(const AttnParams& p, bool prefix, bool suffix, hipS
     if (prefix && p.num_prefix_splits > 0) {
         const dim3 grid(p.N * p.Hq, p.num_prefix_splits);
         if (p.dtype == 0)
-            hipLaunchKernelGGL(attn_plain_kernel<float>, grid, block, 0, s, p, 0, 1);
+            hipLaunchKernelGGL(attn_plain_kernel<float>, grid, block, 0, s, p, p.prefix_slot0, 1);
         else
-            hipLaunchKernelGGL(attn_plain_kernel<uint16_t>, grid, block, 0, s, p, 0, 1);
+            hipLaunchKernelGGL(attn_plain_kernel<uint16_t>, grid, block, 0, s, p, p.prefix_slot0, 1);
     }
     if (suffix && p.num_suffix_chunks > 0) {
         const dim3 grid(p.N * p.Hq, p.num_suffix_chunks);
         if (p.dtype == 0)
-            hipLaunchKernelGGL(attn_plain_kernel<float>, grid, block, 0, s, p, p.num_prefix_splits, 0);
+            hipLaunchKernelGGL(attn_plain_kernel<float>, grid, block, 0, s, p, p.suffix_slot0, 0);
         else
-            hipLaunchKernelGGL(attn_plain_kernel<uint16_t>, grid, block, 0, s, p, p.num_prefix_splits, 0);
+            hipLaunchKernelGGL(attn_plain_kernel<uint16_t>, grid, block, 0, s, p, p.suffix_slot0, 0);
     }
     return hipGetLastError();
 }

@@ -436,7 +436,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     const float l = l_run + __shfl_xor(l_run, 32);
     if (!row_ok)
         return;
-    const long long prow = part_index(p, out_row, split);
+    const long long prow = part_index(p, out_row, p.prefix_slot0 + split);
     if (h == 0)
         p.part_ml[prow] = make_float2(m_run, l);
     // the split's own normalised output, fp16 (l > 0: a split holds at least one token)

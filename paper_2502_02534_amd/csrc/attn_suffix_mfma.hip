@@ -28,9 +28,9 @@ hipError_t launch_attn_suffix_mfma(const AttnParams& p, hipStream_t s)
     const long long total = (long long)p.N * p.Hkv * p.num_suffix_chunks;
     const dim3 grid((unsigned)((total + kWavesPerBlock - 1) / kWavesPerBlock));
     if (p.page_size)
-        hipLaunchKernelGGL(attn_suffix_mfma_kernel<true>, grid, dim3(256), 0, s, p, p.num_prefix_splits);
+        hipLaunchKernelGGL(attn_suffix_mfma_kernel<true>, grid, dim3(256), 0, s, p, p.suffix_slot0);
     else
-        hipLaunchKernelGGL(attn_suffix_mfma_kernel<false>, grid, dim3(256), 0, s, p, p.num_prefix_splits);
+        hipLaunchKernelGGL(attn_suffix_mfma_kernel<false>, grid, dim3(256), 0, s, p, p.suffix_slot0);
     return hipGetLastError();
 }
 

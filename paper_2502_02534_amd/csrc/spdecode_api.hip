@@ -246,6 +246,12 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
     p.suffix_chunk_tokens = pl.suffix_chunk_tokens;
     p.num_suffix_chunks = pl.num_suffix_chunks;
     p.num_slots = pl.num_prefix_splits + pl.num_suffix_chunks;
+    p.prefix_slot0 = 0;
+    p.suffix_slot0 = pl.num_prefix_splits;
+    p.num_levels = 1;
+    for (int l = 0; l < spd::kMaxLevels; ++l)
+        p.mlev[l] = spd::MergeLevel{nullptr, nullptr, 0, 0, 0};
+    p.mlev[0] = spd::MergeLevel{sample_indptr, prefix_lens, desc->num_prompts, pl.prefix_split_tokens, 0};
     p.part_acc = workspace;
     p.part_half = desc->dtype == SPD_BF16 ? 1 : 0;
     p.part_ml = (float2*)((char*)workspace + pl.acc_bytes);
