@@ -133,6 +133,54 @@ SPD_API int shared_prefix_decode_attn(const spd_attn_desc *desc,
                               void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/*
+ * One level of a tree of shared prefixes.  The paper's prompts nest: the base prompt is shared
+ * by every task, the demonstrations by the tasks of an iteration, the task text by its samples
+ * (Sec. "Adaptive self-improvement learning", Alg. 1).  At each level the N samples are cut into
+ * consecutive groups; the samples of a group attend over the group's KV.
+ */
+typedef struct spd_prefix_level {
+    const void *k, *v;              /* device; layout as k_prefix/v_prefix of the plain call */
+    const int32_t *lens;            /* device int32 [num_groups]: tokens per group (0 allowed) */
+    const int32_t *indptr;          /* device int32 [num_groups+1]: token or page-list offsets */
+    const int32_t *page_indices;    /* device, paged KV only */
+    const int32_t *sample_indptr;   /* device int32 [num_groups+1]: group g owns samples
+                                       sample_indptr[g] .. sample_indptr[g+1]-1; covers 0..N */
+    int32_t num_groups;             /* >= 1 */
+    int32_t max_samples_per_group;  /* upper bound; 0 = N */
+    int64_t max_len;                /* host-known upper bound on lens[] */
+} spd_prefix_level;
+
+#define SPD_MAX_PREFIX_LEVELS 4
+
+/* Bytes of workspace the multi-level call needs (0 on invalid arguments).  `levels` is host
+ * memory; only num_groups, max_samples_per_group and max_len are read. */
+SPD_API size_t shared_prefix_decode_attn_levels_workspace_size(const spd_attn_desc *desc,
+                                                       int32_t num_levels,
+                                                       const spd_prefix_level *levels,
+                                                       int64_t max_suffix_len);
+
+/*
+ * Attention of one decode step over a tree of shared prefixes:
+ * out[n, h, :] = softmax(q[n, h] . K^T * scale) V over
+ * [level 0 KV of n's group | level 1 KV of n's group | ... | suffix of n].
+ * With one level this is shared_prefix_decode_attn.  desc->num_prompts and
+ * desc->max_samples_per_prompt are ignored (the levels carry them); desc->stages must be 0;
+ * 1 <= num_levels <= SPD_MAX_PREFIX_LEVELS; `levels` is host memory read during the call.
+ * Everything else as for shared_prefix_decode_attn.  Returns spd_status.
+ */
+SPD_API int shared_prefix_decode_attn_levels(const spd_attn_desc *desc,
+                                     const void *q,
+                                     int32_t num_levels, const spd_prefix_level *levels,
+                                     const void *k_suffix, const void *v_suffix,
+                                     const int32_t *suffix_lens,
+                                     const int32_t *suffix_page_indptr,
+                                     const int32_t *suffix_page_indices,
+                                     int64_t max_suffix_len,
+                                     void *out, float *lse_out,
+                                     void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
 /* Bytes of workspace sample_tokens needs (0 on invalid sizes). */
 SPD_API size_t sample_tokens_workspace_size(int64_t rows, int64_t vocab);
 

@@ -37,6 +37,13 @@ class AttnDesc(ctypes.Structure):
                 ("sm_scale", ctypes.c_float), ("stages", ctypes.c_uint32)]
 
 
+class PrefixLevel(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("lens", ctypes.c_void_p),
+                ("indptr", ctypes.c_void_p), ("page_indices", ctypes.c_void_p),
+                ("sample_indptr", ctypes.c_void_p), ("num_groups", ctypes.c_int32),
+                ("max_samples_per_group", ctypes.c_int32), ("max_len", ctypes.c_int64)]
+
+
 def load() -> ctypes.CDLL:
     """Load the HIP library.  Raises if it has not been built."""
     global _lib
@@ -60,6 +67,11 @@ def load() -> ctypes.CDLL:
     lib.sample_tokens_workspace_size.argtypes = [i64, i64]
     lib.sample_tokens.restype = ctypes.c_int
     lib.sample_tokens.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lp = ctypes.POINTER(PrefixLevel)
+    lib.shared_prefix_decode_attn_levels_workspace_size.restype = sz
+    lib.shared_prefix_decode_attn_levels_workspace_size.argtypes = [dp, ctypes.c_int32, lp, i64]
+    lib.shared_prefix_decode_attn_levels.restype = ctypes.c_int
+    lib.shared_prefix_decode_attn_levels.argtypes = [dp, vp, ctypes.c_int32, lp] + [vp] * 5 + [i64, vp, vp, vp, sz, vp]
     lib.append_suffix_kv.restype = ctypes.c_int
     lib.append_suffix_kv.argtypes = [dp] + [vp] * 7 + [i64, vp, ctypes.c_int32, vp, vp]
     _lib = lib
@@ -137,3 +149,32 @@ def append_suffix_kv(desc: AttnDesc, k_new, v_new, k_suffix, v_suffix, suffix_le
         int(end_token), _ptr(finished), _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "append_suffix_kv")
+
+
+def make_levels(levels):
+    """ctypes array of PrefixLevel from records with tensor fields k, v, lens, indptr, sample_indptr
+    (and optionally page_indices) plus max_samples_per_group and max_len."""
+    arr = (PrefixLevel * len(levels))()
+    for i, lv in enumerate(levels):
+        pages = getattr(lv, "page_indices", None)
+        arr[i] = PrefixLevel(lv.k.data_ptr(), lv.v.data_ptr(), lv.lens.data_ptr(), lv.indptr.data_ptr(),
+                             0 if pages is None else pages.data_ptr(), lv.sample_indptr.data_ptr(),
+                             int(lv.lens.numel()), int(lv.max_samples_per_group), int(lv.max_len))
+    return arr
+
+
+def shared_prefix_decode_attn_levels_workspace_size(desc: AttnDesc, levels, max_suffix_len: int) -> int:
+    return int(load().shared_prefix_decode_attn_levels_workspace_size(ctypes.byref(desc), len(levels), levels,
+                                                                      int(max_suffix_len)))
+
+
+def shared_prefix_decode_attn_levels(desc: AttnDesc, q, levels, k_suffix, v_suffix, suffix_lens,
+                                     suffix_page_indptr, suffix_page_indices, max_suffix_len: int, out, lse_out,
+                                     workspace, stream=None) -> None:
+    rc = load().shared_prefix_decode_attn_levels(
+        ctypes.byref(desc), _ptr(q), len(levels), levels, _ptr(k_suffix), _ptr(v_suffix), _ptr(suffix_lens),
+        _ptr(suffix_page_indptr), _ptr(suffix_page_indices), int(max_suffix_len), _ptr(out), _ptr(lse_out),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "shared_prefix_decode_attn_levels")

@@ -47,6 +47,32 @@ int part_tokens(long long len, int min_tokens, int max_parts, int quantum)
     return (int)t;
 }
 
+// Tokens per split of a prefix level with `groups` groups of at most `spp` samples and lengths up to
+// `max_prefix`, at most `max_splits` splits.
+int plan_prefix_split(const spd_attn_desc* d, int groups, int spp, long long max_prefix, int max_splits)
+{
+    int split;
+    if (d->dtype == SPD_BF16 && d->head_dim == 128) {
+        // tiled path: one workgroup per (group, KV head, row tile, split); enough splits to
+        // occupy every CU once, in multiples of the 64-token tile
+        const int rows = spp * (d->num_q_heads / d->num_kv_heads);
+        const int block_rows = spd::prefix_mfma_block_rows(rows);
+        const long long base = (long long)groups * d->num_kv_heads * ((rows + block_rows - 1) / block_rows);
+        long long want = (256 + base - 1) / base;
+        if (want > max_splits) want = max_splits;
+        long long t = (max_prefix + want - 1) / want;
+        t = (t + 63) / 64 * 64;
+        if (t < 64) t = 64;
+        split = (int)t;
+    } else {
+        split = part_tokens(max_prefix, 256, max_splits, 64);
+    }
+#ifdef SPD_TUNING
+    if (const char* e = getenv("SPD_TUNE_PREFIX_SPLIT")) split = atoi(e);
+#endif
+    return split;
+}
+
 int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix, Plan* pl)
 {
     const int rc = check_desc(d);
@@ -54,25 +80,8 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
         return rc;
     if (max_prefix < 0 || max_suffix < 0 || max_prefix > (1ll << 30) || max_suffix > (1ll << 30))
         return SPD_EINVAL;
-    if (d->dtype == SPD_BF16 && d->head_dim == 128) {
-        // tiled path: one workgroup per (prompt, KV head, row tile, split); enough splits to
-        // occupy every CU once, in multiples of the 64-token tile
-        const int spp = d->max_samples_per_prompt > 0 ? d->max_samples_per_prompt : d->num_samples;
-        const int rows = spp * (d->num_q_heads / d->num_kv_heads);
-        const int block_rows = spd::prefix_mfma_block_rows(rows);
-        const long long base = (long long)d->num_prompts * d->num_kv_heads * ((rows + block_rows - 1) / block_rows);
-        long long want = (256 + base - 1) / base;
-        if (want > 64) want = 64;
-        long long t = (max_prefix + want - 1) / want;
-        t = (t + 63) / 64 * 64;
-        if (t < 64) t = 64;
-        pl->prefix_split_tokens = (int)t;
-    } else {
-        pl->prefix_split_tokens = part_tokens(max_prefix, 256, 64, 64);
-    }
-#ifdef SPD_TUNING
-    if (const char* e = getenv("SPD_TUNE_PREFIX_SPLIT")) pl->prefix_split_tokens = atoi(e);
-#endif
+    const int spp = d->max_samples_per_prompt > 0 ? d->max_samples_per_prompt : d->num_samples;
+    pl->prefix_split_tokens = plan_prefix_split(d, d->num_prompts, spp, max_prefix, 64);
     pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
     {
         // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..320 tokens
@@ -183,6 +192,172 @@ size_t shared_prefix_decode_attn_workspace_size(const spd_attn_desc* desc, int64
     return pl.acc_bytes + pl.ml_bytes + 256;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Plan of a multi-level call: split size and count per level, slot offsets, suffix chunks.
+struct LevelPlan {
+    int split_tokens[SPD_MAX_PREFIX_LEVELS], num_splits[SPD_MAX_PREFIX_LEVELS], slot0[SPD_MAX_PREFIX_LEVELS];
+    int suffix_chunk_tokens, num_suffix_chunks, num_slots;
+    size_t acc_bytes, ml_bytes;
+};
+
+int make_level_plan(const spd_attn_desc* d, int num_levels, const spd_prefix_level* levels, long long max_suffix,
+                    LevelPlan* lp)
+{
+    if (num_levels < 1 || num_levels > SPD_MAX_PREFIX_LEVELS || !levels)
+        return SPD_EINVAL;
+    Plan pl;
+    spd_attn_desc tmp = *d;
+    tmp.num_prompts = 1;
+    tmp.max_samples_per_prompt = 0;
+    const int rc = make_plan(&tmp, 0, max_suffix, &pl);  // validates desc and plans the suffix chunks
+    if (rc != SPD_OK)
+        return rc;
+    lp->suffix_chunk_tokens = pl.suffix_chunk_tokens;
+    lp->num_suffix_chunks = pl.num_suffix_chunks;
+    const int max_splits = 64 / num_levels;  // the merge takes 64 prefix splits in all
+    int slots = 0;
+    for (int l = 0; l < num_levels; ++l) {
+        const spd_prefix_level& L = levels[l];
+        if (L.num_groups < 1 || L.max_samples_per_group < 0 || L.max_len < 0 || L.max_len > (1ll << 30))
+            return SPD_EINVAL;
+        const int spp = L.max_samples_per_group > 0 ? L.max_samples_per_group : d->num_samples;
+        lp->split_tokens[l] = plan_prefix_split(d, L.num_groups, spp, L.max_len, max_splits);
+        lp->num_splits[l] = (int)((L.max_len + lp->split_tokens[l] - 1) / lp->split_tokens[l]);
+        lp->slot0[l] = slots;
+        slots += lp->num_splits[l];
+    }
+    lp->num_slots = slots + lp->num_suffix_chunks;
+    const size_t rows = (size_t)d->num_samples * d->num_q_heads;
+    lp->acc_bytes = align_up((size_t)lp->num_slots * rows * d->head_dim * sizeof(float), 256);
+    lp->ml_bytes = align_up((size_t)lp->num_slots * rows * sizeof(float2), 256);
+    return SPD_OK;
+}
+
+// The attention call proper: any number of prefix levels.  `stages` as in spd_attn_desc.
+int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, const spd_prefix_level* levels,
+                  const LevelPlan& lp, const void* k_suffix, const void* v_suffix, const int32_t* suffix_lens,
+                  const int32_t* suffix_page_indptr, const int32_t* suffix_page_indices, int64_t max_suffix_len,
+                  void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !suffix_lens || !out)
+        return SPD_EINVAL;
+    if (max_suffix_len > 0 && (!k_suffix || !v_suffix))
+        return SPD_EINVAL;
+    if (desc->page_size != 0 && max_suffix_len > 0 && (!suffix_page_indptr || !suffix_page_indices))
+        return SPD_EINVAL;
+    const void* aligned16[] = {q, k_suffix, v_suffix, out};
+    for (const void* ptr : aligned16)
+        if (ptr && misaligned(ptr, 16))
+            return SPD_EINVAL;
+    for (int l = 0; l < num_levels; ++l) {
+        const spd_prefix_level& L = levels[l];
+        if (!L.lens || !L.indptr || !L.sample_indptr)
+            return SPD_EINVAL;
+        if (L.max_len > 0 && (!L.k || !L.v || misaligned(L.k, 16) || misaligned(L.v, 16)))
+            return SPD_EINVAL;
+        if (desc->page_size != 0 && L.max_len > 0 && !L.page_indices)
+            return SPD_EINVAL;
+    }
+    const size_t need = lp.acc_bytes + lp.ml_bytes + 256;
+    if (!workspace || misaligned(workspace, 256) || workspace_bytes < need)
+        return SPD_EWORKSPACE;
+
+    AttnParams p;
+    p.dtype = desc->dtype;
+    p.Hq = desc->num_q_heads;
+    p.Hkv = desc->num_kv_heads;
+    p.D = desc->head_dim;
+    p.G = p.Hq / p.Hkv;
+    p.N = desc->num_samples;
+    p.page_size = desc->page_size;
+    const float scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)p.D);
+    p.scale_log2 = scale * spd::kLog2e;
+    p.q = q;
+    p.k_suffix = k_suffix;
+    p.v_suffix = v_suffix;
+    p.suffix_lens = suffix_lens;
+    p.suffix_page_indptr = suffix_page_indptr;
+    p.suffix_pages = suffix_page_indices;
+    p.max_suffix_len = max_suffix_len;
+    p.suffix_chunk_tokens = lp.suffix_chunk_tokens;
+    p.num_suffix_chunks = lp.num_suffix_chunks;
+    p.num_slots = lp.num_slots;
+    p.suffix_slot0 = lp.num_slots - lp.num_suffix_chunks;
+    p.num_levels = num_levels;
+    for (int l = 0; l < spd::kMaxLevels; ++l)
+        p.mlev[l] = spd::MergeLevel{nullptr, nullptr, 0, 0, 0};
+    for (int l = 0; l < num_levels; ++l)
+        p.mlev[l] = spd::MergeLevel{levels[l].sample_indptr, levels[l].lens, levels[l].num_groups,
+                                    lp.split_tokens[l], lp.slot0[l]};
+    p.part_acc = workspace;
+    p.part_half = desc->dtype == SPD_BF16 ? 1 : 0;
+    p.part_ml = (float2*)((char*)workspace + lp.acc_bytes);
+    p.out = out;
+    p.lse = lse_out;
+
+    const uint32_t stages = desc->stages ? desc->stages
+                                         : (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    // Every level is one prefix pass over its own grouping of the samples; the last level shares
+    // its launch with the suffix pass where the fused kernel takes the shape.
+    for (int l = 0; l < num_levels; ++l) {
+        const spd_prefix_level& L = levels[l];
+        p.k_prefix = L.k;
+        p.v_prefix = L.v;
+        p.prefix_lens = L.lens;
+        p.prefix_indptr = L.indptr;
+        p.prefix_pages = L.page_indices;
+        p.sample_indptr = L.sample_indptr;
+        p.B = L.num_groups;
+        p.max_spp = L.max_samples_per_group > 0 ? L.max_samples_per_group : desc->num_samples;
+        p.prefix_split_tokens = lp.split_tokens[l];
+        p.num_prefix_splits = lp.num_splits[l];
+        p.prefix_slot0 = lp.slot0[l];
+        const bool last = l == num_levels - 1;
+        const bool want_prefix = (stages & SPD_STAGE_PREFIX) != 0;
+        const bool want_suffix = last && (stages & SPD_STAGE_SUFFIX) != 0;
+        const bool suffix_tiled = spd::suffix_mfma_supported(p);
+        const bool prefix_tiled = spd::prefix_mfma_supported(p);
+        e = spd::launch_attn_plain(p, want_prefix && !prefix_tiled, want_suffix && !suffix_tiled, s);
+        if (e != hipSuccess)
+            return SPD_ELAUNCH;
+        bool fused = want_prefix && want_suffix && spd::attn_fused_supported(p);
+#ifdef SPD_TUNING
+        if (getenv("SPD_TUNE_NO_FUSED")) fused = false;
+#endif
+        if (fused) {
+            e = spd::launch_attn_fused(p, s);
+            if (e != hipSuccess)
+                return SPD_ELAUNCH;
+        } else {
+            if (want_prefix && prefix_tiled) {
+                e = spd::launch_attn_prefix_mfma(p, s);
+                if (e != hipSuccess)
+                    return SPD_ELAUNCH;
+            }
+            if (want_suffix && suffix_tiled) {
+                e = spd::launch_attn_suffix_mfma(p, s);
+                if (e != hipSuccess)
+                    return SPD_ELAUNCH;
+            }
+        }
+    }
+    if (stages & SPD_STAGE_MERGE) {
+        e = spd::launch_attn_merge(p, s);
+        if (e != hipSuccess)
+            return SPD_ELAUNCH;
+    }
+    return SPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const void* k_prefix,
                               const void* v_prefix, const int32_t* prefix_lens,
                               const int32_t* prefix_indptr, const int32_t* prefix_page_indices,
@@ -196,105 +371,55 @@ int shared_prefix_decode_attn(const spd_attn_desc* desc, const void* q, const vo
     const int rc = make_plan(desc, max_prefix_len, max_suffix_len, &pl);
     if (rc != SPD_OK)
         return rc;
-    if (!q || !prefix_lens || !prefix_indptr || !sample_indptr || !suffix_lens || !out)
-        return SPD_EINVAL;
-    if (max_prefix_len > 0 && (!k_prefix || !v_prefix))
-        return SPD_EINVAL;
-    if (max_suffix_len > 0 && (!k_suffix || !v_suffix))
-        return SPD_EINVAL;
-    if (desc->page_size != 0) {
-        if (max_prefix_len > 0 && !prefix_page_indices)
-            return SPD_EINVAL;
-        if (max_suffix_len > 0 && (!suffix_page_indptr || !suffix_page_indices))
-            return SPD_EINVAL;
-    }
-    const void* aligned16[] = {q, k_prefix, v_prefix, k_suffix, v_suffix, out};
-    for (const void* ptr : aligned16)
-        if (ptr && misaligned(ptr, 16))
-            return SPD_EINVAL;
-    const size_t need = pl.acc_bytes + pl.ml_bytes + 256;
-    if (!workspace || misaligned(workspace, 256) || workspace_bytes < need)
-        return SPD_EWORKSPACE;
+    // one level of shared prefixes, planned exactly as spd_attn_plan reports it
+    spd_prefix_level level;
+    level.k = k_prefix;
+    level.v = v_prefix;
+    level.lens = prefix_lens;
+    level.indptr = prefix_indptr;
+    level.page_indices = prefix_page_indices;
+    level.sample_indptr = sample_indptr;
+    level.num_groups = desc->num_prompts;
+    level.max_samples_per_group = desc->max_samples_per_prompt;
+    level.max_len = max_prefix_len;
+    LevelPlan lp;
+    lp.split_tokens[0] = pl.prefix_split_tokens;
+    lp.num_splits[0] = pl.num_prefix_splits;
+    lp.slot0[0] = 0;
+    lp.suffix_chunk_tokens = pl.suffix_chunk_tokens;
+    lp.num_suffix_chunks = pl.num_suffix_chunks;
+    lp.num_slots = pl.num_prefix_splits + pl.num_suffix_chunks;
+    lp.acc_bytes = pl.acc_bytes;
+    lp.ml_bytes = pl.ml_bytes;
+    return run_attention(desc, q, 1, &level, lp, k_suffix, v_suffix, suffix_lens, suffix_page_indptr,
+                         suffix_page_indices, max_suffix_len, out, lse_out, workspace, workspace_bytes, stream);
+}
 
-    AttnParams p;
-    p.dtype = desc->dtype;
-    p.Hq = desc->num_q_heads;
-    p.Hkv = desc->num_kv_heads;
-    p.D = desc->head_dim;
-    p.G = p.Hq / p.Hkv;
-    p.B = desc->num_prompts;
-    p.N = desc->num_samples;
-    p.max_spp = desc->max_samples_per_prompt > 0 ? desc->max_samples_per_prompt : desc->num_samples;
-    p.page_size = desc->page_size;
-    const float scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)p.D);
-    p.scale_log2 = scale * spd::kLog2e;
-    p.q = q;
-    p.k_prefix = k_prefix;
-    p.v_prefix = v_prefix;
-    p.prefix_lens = prefix_lens;
-    p.prefix_indptr = prefix_indptr;
-    p.prefix_pages = prefix_page_indices;
-    p.sample_indptr = sample_indptr;
-    p.k_suffix = k_suffix;
-    p.v_suffix = v_suffix;
-    p.suffix_lens = suffix_lens;
-    p.suffix_page_indptr = suffix_page_indptr;
-    p.suffix_pages = suffix_page_indices;
-    p.max_suffix_len = max_suffix_len;
-    p.prefix_split_tokens = pl.prefix_split_tokens;
-    p.num_prefix_splits = pl.num_prefix_splits;
-    p.suffix_chunk_tokens = pl.suffix_chunk_tokens;
-    p.num_suffix_chunks = pl.num_suffix_chunks;
-    p.num_slots = pl.num_prefix_splits + pl.num_suffix_chunks;
-    p.prefix_slot0 = 0;
-    p.suffix_slot0 = pl.num_prefix_splits;
-    p.num_levels = 1;
-    for (int l = 0; l < spd::kMaxLevels; ++l)
-        p.mlev[l] = spd::MergeLevel{nullptr, nullptr, 0, 0, 0};
-    p.mlev[0] = spd::MergeLevel{sample_indptr, prefix_lens, desc->num_prompts, pl.prefix_split_tokens, 0};
-    p.part_acc = workspace;
-    p.part_half = desc->dtype == SPD_BF16 ? 1 : 0;
-    p.part_ml = (float2*)((char*)workspace + pl.acc_bytes);
-    p.out = out;
-    p.lse = lse_out;
+size_t shared_prefix_decode_attn_levels_workspace_size(const spd_attn_desc* desc, int32_t num_levels,
+                                                       const spd_prefix_level* levels, int64_t max_suffix_len)
+{
+    LevelPlan lp;
+    if (!desc || make_level_plan(desc, num_levels, levels, max_suffix_len, &lp) != SPD_OK)
+        return 0;
+    return lp.acc_bytes + lp.ml_bytes + 256;
+}
 
-    const uint32_t stages = desc->stages ? desc->stages
-                                         : (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE);
-    hipStream_t s = (hipStream_t)stream;
-    hipError_t e = hipSuccess;
-    const bool suffix_tiled = spd::suffix_mfma_supported(p);
-    const bool prefix_tiled = spd::prefix_mfma_supported(p);
-    e = spd::launch_attn_plain(p, (stages & SPD_STAGE_PREFIX) && !prefix_tiled,
-                               (stages & SPD_STAGE_SUFFIX) && !suffix_tiled, s);
-    if (e != hipSuccess)
-        return SPD_ELAUNCH;
-    const bool both = (stages & SPD_STAGE_PREFIX) && (stages & SPD_STAGE_SUFFIX);
-    bool fused = both && spd::attn_fused_supported(p);
-#ifdef SPD_TUNING
-    if (getenv("SPD_TUNE_NO_FUSED")) fused = false;
-#endif
-    if (fused) {
-        e = spd::launch_attn_fused(p, s);
-        if (e != hipSuccess)
-            return SPD_ELAUNCH;
-    } else {
-        if ((stages & SPD_STAGE_PREFIX) && prefix_tiled) {
-            e = spd::launch_attn_prefix_mfma(p, s);
-            if (e != hipSuccess)
-                return SPD_ELAUNCH;
-        }
-        if ((stages & SPD_STAGE_SUFFIX) && suffix_tiled) {
-            e = spd::launch_attn_suffix_mfma(p, s);
-            if (e != hipSuccess)
-                return SPD_ELAUNCH;
-        }
-    }
-    if (stages & SPD_STAGE_MERGE) {
-        e = spd::launch_attn_merge(p, s);
-        if (e != hipSuccess)
-            return SPD_ELAUNCH;
-    }
-    return SPD_OK;
+int shared_prefix_decode_attn_levels(const spd_attn_desc* desc, const void* q, int32_t num_levels,
+                                     const spd_prefix_level* levels, const void* k_suffix, const void* v_suffix,
+                                     const int32_t* suffix_lens, const int32_t* suffix_page_indptr,
+                                     const int32_t* suffix_page_indices, int64_t max_suffix_len, void* out,
+                                     float* lse_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!desc)
+        return SPD_EINVAL;
+    if (desc->stages != 0)
+        return SPD_EINVAL;
+    LevelPlan lp;
+    const int rc = make_level_plan(desc, num_levels, levels, max_suffix_len, &lp);
+    if (rc != SPD_OK)
+        return rc;
+    return run_attention(desc, q, num_levels, levels, lp, k_suffix, v_suffix, suffix_lens, suffix_page_indptr,
+                         suffix_page_indices, max_suffix_len, out, lse_out, workspace, workspace_bytes, stream);
 }
 
 size_t sample_tokens_workspace_size(int64_t rows, int64_t vocab)

@@ -153,3 +153,42 @@ class DecodeLoop:
         self.out_steps.index_copy_(0, idx, a.out.unsqueeze(0))
         self.lens_steps.index_copy_(0, idx, a.suffix_lens.unsqueeze(0))
         self.step.add_(1)
+
+
+@dataclasses.dataclass
+class DeviceLevel:
+    k: torch.Tensor
+    v: torch.Tensor
+    lens: torch.Tensor
+    indptr: torch.Tensor
+    sample_indptr: torch.Tensor
+    max_samples_per_group: int
+    max_len: int
+
+
+class DeviceCascade:
+    """A CascadeInputs record on the GPU and the multi-level attention call on it."""
+
+    def __init__(self, inp, device="cuda:0"):
+        sp = inp.spec
+        bf16 = sp.dtype == "bf16"
+        n, hq, d = inp.q.shape
+        self.desc = B.make_desc(dtype=B.SPD_BF16 if bf16 else B.SPD_F32, num_q_heads=hq,
+                                num_kv_heads=sp.num_kv_heads, head_dim=d, num_prompts=1, num_samples=n)
+        self.q = _dev(inp.q, device, bf16)
+        self.levels = [DeviceLevel(_dev(lv.k, device, bf16), _dev(lv.v, device, bf16), _dev(lv.lens, device),
+                                   _dev(lv.indptr, device), _dev(lv.sample_indptr, device),
+                                   lv.max_samples_per_group, lv.max_len) for lv in inp.levels]
+        self.level_array = B.make_levels(self.levels)
+        self.k_suffix, self.v_suffix = _dev(inp.k_suffix, device, bf16), _dev(inp.v_suffix, device, bf16)
+        self.suffix_lens = _dev(inp.suffix_lens, device)
+        self.max_suffix_len = inp.max_suffix_len
+        self.out = torch.empty((n, hq, d), dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+        self.lse = torch.empty((n, hq), dtype=torch.float32, device=device)
+        nbytes = B.shared_prefix_decode_attn_levels_workspace_size(self.desc, self.level_array, self.max_suffix_len)
+        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+    def run(self, stream=None) -> None:
+        B.shared_prefix_decode_attn_levels(self.desc, self.q, self.level_array, self.k_suffix, self.v_suffix,
+                                           self.suffix_lens, None, None, self.max_suffix_len, self.out, self.lse,
+                                           self.workspace, stream)

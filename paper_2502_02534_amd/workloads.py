@@ -224,3 +224,80 @@ def small_spec(**kw) -> WorkloadSpec:
              vocab=1000, logit_sigma=3.0, temperature=(0.7, 0.7), top_p=0.9)
     d.update(kw)
     return WorkloadSpec(**d)
+
+
+@dataclasses.dataclass
+class PrefixLevel:
+    """One level of a tree of shared prefixes (contiguous KV)."""
+    k: np.ndarray               # [sum lens, Hkv, D]
+    v: np.ndarray
+    lens: np.ndarray            # int32 [groups]
+    indptr: np.ndarray          # int32 [groups+1] token offsets
+    sample_indptr: np.ndarray   # int32 [groups+1]
+    max_samples_per_group: int
+    max_len: int
+
+
+@dataclasses.dataclass
+class CascadeInputs:
+    """Inputs of one decode-attention call over several levels of shared prefixes, and the same
+    problem written as a single level (`flat`): every distinct chain of groups becomes one prompt
+    whose prefix is the concatenation of its groups' KV, which is what the call must equal."""
+    spec: WorkloadSpec
+    q: np.ndarray
+    levels: list
+    k_suffix: np.ndarray
+    v_suffix: np.ndarray
+    suffix_lens: np.ndarray
+    max_suffix_len: int
+    flat: AttnInputs
+
+
+def make_cascade_inputs(group_sizes, len_ranges, *, dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128,
+                        suffix_len=(0, 70), seed=0) -> CascadeInputs:
+    """`group_sizes[l]` lists the number of samples in each consecutive group of level l (each list
+    sums to N); `len_ranges[l]` is the (lo, hi) range of that level's group lengths."""
+    N = int(sum(group_sizes[0]))
+    assert all(int(sum(g)) == N for g in group_sizes)
+    rng = np.random.default_rng([250202534, seed])
+    r_q, r_s, r_len = rng.spawn(3)
+    Hq, Hkv, D = num_q_heads, num_kv_heads, head_dim
+    q = _normal(r_q, (N, Hq, D), dtype)
+    levels = []
+    for l, sizes in enumerate(group_sizes):
+        r_k, r_v, r_l = rng.spawn(3)
+        lens = _lens(r_l, len_ranges[l], len(sizes))
+        indptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        total = max(int(indptr[-1]), 1)
+        levels.append(PrefixLevel(_normal(r_k, (total, Hkv, D), dtype), _normal(r_v, (total, Hkv, D), dtype), lens,
+                                  indptr, np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32),
+                                  int(max(sizes)), int(len_ranges[l][1])))
+    ls_max = int(suffix_len[1])
+    suffix_lens = _lens(r_len, suffix_len, N)
+    r_ks, r_vs = r_s.spawn(2)
+    k_suffix = _normal(r_ks, (N, max(ls_max, 1), Hkv, D), dtype)
+    v_suffix = _normal(r_vs, (N, max(ls_max, 1), Hkv, D), dtype)
+    # the same problem as one level: cut the samples wherever any level starts a new group
+    cuts = sorted(set(int(c) for lv in levels for c in lv.sample_indptr))
+    flat_k, flat_v, flat_lens = [], [], []
+    for a in cuts[:-1]:
+        ks, vs = [], []
+        for lv in levels:
+            g = int(np.searchsorted(lv.sample_indptr, a, side="right") - 1)
+            ks.append(lv.k[lv.indptr[g]:lv.indptr[g] + lv.lens[g]])
+            vs.append(lv.v[lv.indptr[g]:lv.indptr[g] + lv.lens[g]])
+        flat_k.append(np.concatenate(ks))
+        flat_v.append(np.concatenate(vs))
+        flat_lens.append(flat_k[-1].shape[0])
+    flat_lens = np.asarray(flat_lens, dtype=np.int32)
+    fk = np.concatenate(flat_k) if sum(flat_lens) else np.zeros((1, Hkv, D), dtype=q.dtype)
+    fv = np.concatenate(flat_v) if sum(flat_lens) else np.zeros((1, Hkv, D), dtype=q.dtype)
+    sizes_flat = np.diff(np.asarray(cuts))
+    spec = small_spec(dtype=dtype, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, num_prompts=len(sizes_flat),
+                      samples_per_prompt=int(sizes_flat.max()), prefix_len=(0, int(max(flat_lens.max(), 1))),
+                      suffix_len=suffix_len)
+    spec = dataclasses.replace(spec, name="cascade")
+    flat = AttnInputs(spec, q, fk, fv, flat_lens, np.concatenate([[0], np.cumsum(flat_lens)]).astype(np.int32),
+                      np.asarray(cuts, dtype=np.int32), k_suffix, v_suffix, suffix_lens, max(ls_max, 1),
+                      int(max(flat_lens.max(), 1)))
+    return CascadeInputs(spec, q, levels, k_suffix, v_suffix, suffix_lens, max(ls_max, 1), flat)

@@ -1,0 +1,55 @@
+"""Attention over a tree of shared prefixes (`shared_prefix_decode_attn_levels`): the paper's prompts
+nest (base prompt shared by all tasks, demonstrations by an iteration's tasks, task text by its
+samples); the result must equal plain attention over each sample's concatenated chain of prefixes,
+which is what the CPU checker computes on the flattened problem."""
+import numpy as np
+import pytest
+
+from paper_2502_02534_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+CASES = [
+    # two levels: one root shared by all 12 samples, three leaf groups
+    dict(group_sizes=[[12], [5, 4, 3]], len_ranges=[(300, 300), (1, 200)], suffix_len=(0, 60)),
+    # three levels, bf16, enough rows per KV head at every level for the tiled and the fused kernels
+    dict(group_sizes=[[72], [40, 32], [20, 20, 16, 16]], len_ranges=[(1500, 1500), (100, 700), (0, 300)],
+         num_q_heads=32, num_kv_heads=8, suffix_len=(0, 200)),
+    # groups that do not nest (any consecutive grouping is allowed), an empty level, no suffix at all
+    dict(group_sizes=[[7, 9], [4, 8, 4], [16]], len_ranges=[(10, 90), (0, 130), (0, 0)], suffix_len=(0, 0)),
+    # fp32 path, four levels
+    dict(group_sizes=[[6], [3, 3], [2, 2, 2], [1] * 6], len_ranges=[(70, 70), (1, 40), (0, 33), (0, 9)],
+         dtype="f32", num_q_heads=4, num_kv_heads=2, head_dim=64, suffix_len=(0, 20)),
+]
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2502_02534_amd import binding, device
+    binding.load()
+    return device
+
+
+@pytest.mark.parametrize("i", range(len(CASES)))
+def test_cascade_equals_attention_over_concatenated_prefixes(dev, oracle, i):
+    print(f"cascade case {i}: {CASES[i]}", flush=True)
+    inp = W.make_cascade_inputs(seed=900 + i, **CASES[i])
+    d = dev.DeviceCascade(inp)
+    d.out.fill_(float("nan"))
+    d.run()
+    torch.cuda.synchronize()
+    out = d.out.float().cpu().numpy().astype(np.float64)
+    lse = d.lse.cpu().numpy().astype(np.float64)
+    ref_out, ref_lse = oracle.attention_inputs(inp.flat)
+    err = np.abs(out - ref_out)
+    if inp.spec.dtype == "f32":
+        assert np.all(err <= 1e-5 * np.abs(ref_out) + 1e-6), err.max()
+    else:
+        assert err.max() <= 2e-2, err.max()
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(ref_lse))
+    assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-4 + (0 if inp.spec.dtype == "f32" else 2e-3))
+    print(f"  max abs err {err.max():.3e}")
