@@ -302,9 +302,16 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
                                          : (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    // Every level is one prefix pass over its own grouping of the samples; the last level shares
-    // its launch with the suffix pass where the fused kernel takes the shape.
-    for (int l = 0; l < num_levels; ++l) {
+    // Every level is one prefix pass over its own grouping of the samples.  The level with the most
+    // tokens shares its launch with the suffix pass (where the fused kernel takes the shape), so
+    // that the suffix stream overlaps with as much matrix work as possible; it is launched last.
+    int with_suffix = 0;
+    for (int l = 1; l < num_levels; ++l)
+        if (levels[l].max_len > levels[with_suffix].max_len)
+            with_suffix = l;
+    for (int step = 0; step < num_levels; ++step) {
+        // order: every other level first, then the one that carries the suffix pass
+        const int l = step == num_levels - 1 ? with_suffix : (step < with_suffix ? step : step + 1);
         const spd_prefix_level& L = levels[l];
         p.k_prefix = L.k;
         p.v_prefix = L.v;
@@ -317,7 +324,7 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
         p.prefix_split_tokens = lp.split_tokens[l];
         p.num_prefix_splits = lp.num_splits[l];
         p.prefix_slot0 = lp.slot0[l];
-        const bool last = l == num_levels - 1;
+        const bool last = l == with_suffix;
         const bool want_prefix = (stages & SPD_STAGE_PREFIX) != 0;
         const bool want_suffix = last && (stages & SPD_STAGE_SUFFIX) != 0;
         const bool suffix_tiled = spd::suffix_mfma_supported(p);
