@@ -104,3 +104,39 @@ def test_plan_invariants(lib, samples, hq, hkv, max_prefix, max_suffix):
         assert max_suffix > chunk * (nchunk - 1)
     ws = B.shared_prefix_decode_attn_workspace_size(desc, max_prefix, max_suffix)
     assert ws >= (nsplit + nchunk) * samples * hq * (128 * 2 + 8)
+
+
+def _levels(B, specs):
+    arr = (B.PrefixLevel * len(specs))()
+    for i, (groups, spg, max_len, ptr) in enumerate(specs):
+        arr[i] = B.PrefixLevel(ptr, ptr, ptr, ptr, 0, ptr, groups, spg, max_len)
+    return arr
+
+
+def test_levels_and_append_entry_points_check_their_arguments(lib):
+    from paper_2502_02534_amd import binding as B
+    d = B.make_desc(dtype=B.SPD_BF16, num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1, num_samples=64)
+    z = ctypes.c_void_p(0)
+    one = 256   # never dereferenced: the checks below fail first
+    lv = _levels(B, [(1, 64, 4096, one), (4, 16, 700, one)])
+    ws = B.shared_prefix_decode_attn_levels_workspace_size(d, lv, 512)
+    single = B.shared_prefix_decode_attn_workspace_size(d, 4096, 512)
+    assert ws > 0 and single > 0
+    # more levels than supported, a level without groups, and stage masks are rejected
+    too_many = _levels(B, [(1, 64, 64, one)] * 5)
+    assert B.shared_prefix_decode_attn_levels_workspace_size(d, too_many, 512) == 0
+    assert B.shared_prefix_decode_attn_levels_workspace_size(d, _levels(B, [(0, 0, 64, one)]), 512) == 0
+    o = ctypes.c_void_p(one)
+    rc = lib.shared_prefix_decode_attn_levels(ctypes.byref(d), o, 2, lv, o, o, o, z, z, 512, o, z, z, 0, z)
+    assert rc == 3                                        # no workspace
+    rc = lib.shared_prefix_decode_attn_levels(ctypes.byref(d), z, 2, lv, o, o, o, z, z, 512, o, z, o, ws, z)
+    assert rc == 1                                        # no queries
+    staged = B.make_desc(dtype=B.SPD_BF16, num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1,
+                         num_samples=64, stages=B.STAGE_PREFIX)
+    rc = lib.shared_prefix_decode_attn_levels(ctypes.byref(staged), o, 2, lv, o, o, o, z, z, 512, o, z, o, ws, z)
+    assert rc == 1
+    # append: null tensors and a paged description without page tables
+    assert lib.append_suffix_kv(ctypes.byref(d), z, z, z, z, z, z, z, 512, z, -1, z, z) == 1
+    paged = B.make_desc(dtype=B.SPD_BF16, num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1,
+                        num_samples=64, page_size=16)
+    assert lib.append_suffix_kv(ctypes.byref(paged), o, o, o, o, o, z, z, 512, z, -1, z, z) == 1
