@@ -5,8 +5,9 @@
 // 80 KB of LDS carries both, two workgroups per CU: the first workgroups run the prefix body
 // (four wavefronts, 128 rows, K ring of 2 and V ring of 3 tiles, copies one tile ahead), the
 // rest run the suffix body (four wavefront items, their private K tiles carved out of the same
-// LDS).  Workgroups start in index order, so every CU first gets one prefix workgroup and then,
-// beside it, suffix workgroups: each SIMD holds one wavefront that multiplies and one that
+// LDS).  Workgroups start in index order; the prefix workgroups come first (or, when there are
+// more of them than CUs, evenly spread through the grid), so that a CU holds one prefix workgroup
+// and, beside it, suffix workgroups: each SIMD has one wavefront that multiplies and one that
 // streams, HBM is busy during the prefix pass, and there is no launch (with its ramp and tail)
 // between the two passes.  Both bodies are the ones the separate kernels use.
 //
@@ -25,17 +26,32 @@ static_assert(kFusedWaves * suffix_impl::kWaveLdsBytes <= kFusedLds, "suffix til
 
 template <bool PAGED>
 __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_fused_kernel(
-    AttnParams p, int prefix_blocks, int rowtiles)
+    AttnParams p, int prefix_blocks, int rowtiles, int spread)
 {
     __shared__ uint4 lds[kFusedLds / 16];
-    const int blk = blockIdx.x;
-    if (blk < prefix_blocks) {
-        const int split = blk % p.num_prefix_splits;
-        const int rest = blk / p.num_prefix_splits;
+    // Which role a workgroup plays.  With at most one prefix workgroup per CU they simply come
+    // first.  With more, they are spread evenly through the grid (of the first n workgroups,
+    // floor(n P / T) are prefix workgroups), so that CUs keep holding one of each kind instead of
+    // two prefix workgroups.
+    int pidx;       // index among the prefix workgroups, or -1
+    long long sidx; // index among the suffix workgroups
+    if (spread) {
+        const long long blk = blockIdx.x, total = gridDim.x;
+        const int before = (int)(blk * prefix_blocks / total);
+        pidx = (int)((blk + 1) * prefix_blocks / total) > before ? before : -1;
+        sidx = blk - before;
+    } else {
+        pidx = (int)blockIdx.x < prefix_blocks ? (int)blockIdx.x : -1;
+        sidx = (long long)blockIdx.x - prefix_blocks;
+    }
+    if (pidx >= 0) {
+        // split fastest, then row tile, then (group, KV head): the order of the 3-D prefix grid
+        const int split = pidx % p.num_prefix_splits;
+        const int rest = pidx / p.num_prefix_splits;
         prefix_impl::prefix_body<kFusedWaves, PAGED, 2, 3, 1>(p, lds, split, rest % rowtiles, rest / rowtiles);
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const long long item = (long long)(blk - prefix_blocks) * kFusedWaves + wave;
+        const long long item = sidx * kFusedWaves + wave;
         typedef uint4 (*wave_tile_t)[suffix_impl::kRowU4];
         suffix_impl::suffix_body<PAGED>(
             p, p.suffix_slot0, item,
@@ -61,10 +77,13 @@ hipError_t launch_attn_fused(const AttnParams& p, hipStream_t s)
     if (prefix_blocks + suffix_blocks > 0x7fffffffLL)
         return hipErrorInvalidValue;
     const dim3 grid((unsigned)(prefix_blocks + suffix_blocks));
+    const int spread = prefix_blocks > 256 ? 1 : 0;  // more prefix workgroups than CUs
     if (p.page_size)
-        hipLaunchKernelGGL(attn_fused_kernel<true>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles);
+        hipLaunchKernelGGL(attn_fused_kernel<true>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles,
+                           spread);
     else
-        hipLaunchKernelGGL(attn_fused_kernel<false>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles);
+        hipLaunchKernelGGL(attn_fused_kernel<false>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles,
+                           spread);
     return hipGetLastError();
 }
 

@@ -7,7 +7,7 @@ namespace {
 using namespace prefix_impl;
 
 // 128-row workgroups (4 wavefronts) take the short rings (80 KB) so that two of them share a CU;
-// 64-row workgroups (2 wavefronts) keep the long rings, copies two tiles ahead.
+// the others (2 or 8 wavefronts) keep the long rings, copies two tiles ahead.
 template <int WAVES, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES == 4 ? 2 : 1, 2))) void
 attn_prefix_mfma_kernel(AttnParams p)
@@ -51,8 +51,16 @@ hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s)
 {
     if (p.num_prefix_splits <= 0)
         return hipSuccess;
-    if (prefix_mfma_block_rows(p.max_spp * p.G) == 128)
+    if (prefix_mfma_block_rows(p.max_spp * p.G) == 128) {
+        // On its own (no suffix workgroups to share a CU with) a matrix-bound pass does better with
+        // 256-row workgroups and the long rings, provided that still gives most CUs a workgroup;
+        // the split plan does not depend on the row tile.
+        const long long wide_blocks =
+            (long long)p.num_prefix_splits * ((p.max_spp * p.G + 255) / 256) * p.B * p.Hkv;
+        if (p.max_spp * p.G > 128 && wide_blocks >= 192)
+            return launch_waves<8>(p, s);
         return launch_waves<4>(p, s);
+    }
     return launch_waves<2>(p, s);
 }
 
