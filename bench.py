@@ -51,7 +51,7 @@ def main() -> int:
                     help="also run a plain 256 MiB device copy three times (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only; --gpus must be 1", file=sys.stderr)
         return 2
 
     import numpy as np
