@@ -26,13 +26,14 @@ static_assert(kFusedWaves * suffix_impl::kWaveLdsBytes <= kFusedLds, "suffix til
 
 template <bool PAGED>
 __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_fused_kernel(
-    AttnParams p, int prefix_blocks, int rowtiles, int spread)
+    AttnParams p, FusedLevels fl, int spread)
 {
     __shared__ uint4 lds[kFusedLds / 16];
     // Which role a workgroup plays.  With at most one prefix workgroup per CU they simply come
     // first.  With more, they are spread evenly through the grid (of the first n workgroups,
     // floor(n P / T) are prefix workgroups), so that CUs keep holding one of each kind instead of
     // two prefix workgroups.
+    const int prefix_blocks = fl.first_block[fl.num_levels];
     int pidx;       // index among the prefix workgroups, or -1
     long long sidx; // index among the suffix workgroups
     if (spread) {
@@ -45,10 +46,19 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
         sidx = (long long)blockIdx.x - prefix_blocks;
     }
     if (pidx >= 0) {
-        // split fastest, then row tile, then (group, KV head): the order of the 3-D prefix grid
-        const int split = pidx % p.num_prefix_splits;
-        const int rest = pidx / p.num_prefix_splits;
-        prefix_impl::prefix_body<kFusedWaves, PAGED, 2, 3, 1>(p, lds, split, rest % rowtiles, rest / rowtiles);
+        // the prefix level this workgroup belongs to; within a level: split fastest, then row tile,
+        // then (group, KV head)
+        int l = 0;
+#pragma unroll
+        for (int k = 1; k < kMaxLevels; ++k)
+            if (k < fl.num_levels && pidx >= fl.first_block[k])
+                l = k;
+        const PrefixLevelParams& lv = fl.level[l];
+        const int local = pidx - fl.first_block[l];
+        const int split = local % lv.num_splits;
+        const int rest = local / lv.num_splits;
+        prefix_impl::prefix_body<kFusedWaves, PAGED, 2, 3, 1>(p, lv, lds, split, rest % lv.rowtiles,
+                                                              rest / lv.rowtiles);
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const long long item = sidx * kFusedWaves + wave;
@@ -57,6 +67,22 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
             p, p.suffix_slot0, item,
             (wave_tile_t)((char*)lds + (size_t)wave * suffix_impl::kWaveLdsBytes));
     }
+}
+
+hipError_t launch_fused(const AttnParams& p, const FusedLevels& fl, hipStream_t s)
+{
+    const long long prefix_blocks = fl.first_block[fl.num_levels];
+    const long long items = (long long)p.N * p.Hkv * p.num_suffix_chunks;
+    const long long suffix_blocks = (items + kFusedWaves - 1) / kFusedWaves;
+    if (prefix_blocks + suffix_blocks > 0x7fffffffLL)
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(prefix_blocks + suffix_blocks));
+    const int spread = prefix_blocks > 256 ? 1 : 0;  // more prefix workgroups than CUs
+    if (p.page_size)
+        hipLaunchKernelGGL(attn_fused_kernel<true>, grid, dim3(kFusedWaves * 64), 0, s, p, fl, spread);
+    else
+        hipLaunchKernelGGL(attn_fused_kernel<false>, grid, dim3(kFusedWaves * 64), 0, s, p, fl, spread);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -70,21 +96,38 @@ bool attn_fused_supported(const AttnParams& p)
 
 hipError_t launch_attn_fused(const AttnParams& p, hipStream_t s)
 {
+    FusedLevels fl;
+    fl.num_levels = 1;
     const int rowtiles = (p.max_spp * p.G + 127) / 128;
-    const long long prefix_blocks = (long long)p.num_prefix_splits * rowtiles * p.B * p.Hkv;
-    const long long items = (long long)p.N * p.Hkv * p.num_suffix_chunks;
-    const long long suffix_blocks = (items + kFusedWaves - 1) / kFusedWaves;
-    if (prefix_blocks + suffix_blocks > 0x7fffffffLL)
+    fl.level[0] = prefix_impl::level_of(p, rowtiles);
+    fl.first_block[0] = 0;
+    const long long blocks = (long long)p.num_prefix_splits * rowtiles * p.B * p.Hkv;
+    if (blocks > 0x7fffffffLL)
         return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(prefix_blocks + suffix_blocks));
-    const int spread = prefix_blocks > 256 ? 1 : 0;  // more prefix workgroups than CUs
-    if (p.page_size)
-        hipLaunchKernelGGL(attn_fused_kernel<true>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles,
-                           spread);
-    else
-        hipLaunchKernelGGL(attn_fused_kernel<false>, grid, dim3(kFusedWaves * 64), 0, s, p, (int)prefix_blocks, rowtiles,
-                           spread);
-    return hipGetLastError();
+    for (int l = 1; l <= kMaxLevels; ++l)
+        fl.first_block[l] = (int)blocks;
+    return launch_fused(p, fl, s);
+}
+
+// Several prefix levels and the suffix pass in one launch: every level must be one the 128-row
+// prefix body takes, with at least one split.
+bool attn_fused_levels_supported(const AttnParams& p, const FusedLevels& fl)
+{
+    if (!suffix_mfma_supported(p) || p.dtype != 1 || p.D != 128 || p.num_suffix_chunks <= 0)
+        return false;
+    if (fl.num_levels < 1 || fl.num_levels > kMaxLevels)
+        return false;
+    for (int l = 0; l < fl.num_levels; ++l) {
+        const PrefixLevelParams& lv = fl.level[l];
+        if (lv.num_splits <= 0 || lv.split_tokens % 64 != 0 || (long long)lv.groups * p.Hkv > 65535)
+            return false;
+    }
+    return true;
+}
+
+hipError_t launch_attn_fused_levels(const AttnParams& p, const FusedLevels& fl, hipStream_t s)
+{
+    return launch_fused(p, fl, s);
 }
 
 }  // namespace spd

@@ -104,16 +104,36 @@ __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int,
     (f(std::integral_constant<int, I>{}), ...);
 }
 
+// The prefix level that the prefix fields of `p` describe.
+__host__ __device__ inline PrefixLevelParams level_of(const AttnParams& p, int rowtiles)
+{
+    PrefixLevelParams lv;
+    lv.k = p.k_prefix;
+    lv.v = p.v_prefix;
+    lv.lens = p.prefix_lens;
+    lv.indptr = p.prefix_indptr;
+    lv.pages = p.prefix_pages;
+    lv.sample_indptr = p.sample_indptr;
+    lv.split_tokens = p.prefix_split_tokens;
+    lv.num_splits = p.num_prefix_splits;
+    lv.slot0 = p.prefix_slot0;
+    lv.rowtiles = rowtiles;
+    lv.groups = p.B;
+    return lv;
+}
+
 // LDS of a workgroup: KS slots for K tiles followed by VS slots for V tiles.
 constexpr int prefix_lds_bytes(int KS, int VS) { return (KS + VS) * kTileBytes; }
 
-// Body of one workgroup of WAVES wavefronts: (split, rowtile, z = prompt * Hkv + KV head).  `lds` is
+// Body of one workgroup of WAVES wavefronts for prefix level `lv`: (split, rowtile,
+// z = group * Hkv + KV head).  `lds` is
 // prefix_lds_bytes(KS, VS) of LDS; every wavefront of the workgroup must call it (it uses
 // workgroup barriers).  Copies run AHEAD tiles ahead of the tile in use.  K of tile t is read
 // in iteration t and V of tile t in iteration t + 1, and the copies of tile t + AHEAD start at
 // the top of iteration t, so the rings need KS >= AHEAD + 1 and VS >= AHEAD + 2 slots.
 template <int WAVES, bool PAGED, int KS = 4, int VS = 4, int AHEAD = 2>
-__device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int split, int rowtile, int z)
+__device__ __forceinline__ void prefix_body(const AttnParams& p, const PrefixLevelParams& lv, uint4* lds, int split,
+                                            int rowtile, int z)
 {
     static_assert(AHEAD == 1 || AHEAD == 2, "copy distance");
     static_assert(KS >= AHEAD + 1 && VS >= AHEAD + 2, "rings too short for the copy distance");
@@ -125,23 +145,23 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     const int col = lane & 31, h = lane >> 5;
 
     const int b = z / p.Hkv, j = z % p.Hkv;
-    const int s0 = p.sample_indptr[b];
-    const int rows_b = (p.sample_indptr[b + 1] - s0) * p.G;
+    const int s0 = lv.sample_indptr[b];
+    const int rows_b = (lv.sample_indptr[b + 1] - s0) * p.G;
     const int row0 = rowtile * 32 * WAVES;
-    const int Lp = p.prefix_lens[b];
-    const int t0 = split * p.prefix_split_tokens;
-    const int t1 = min(Lp, t0 + p.prefix_split_tokens);
+    const int Lp = lv.lens[b];
+    const int t0 = split * lv.split_tokens;
+    const int t1 = min(Lp, t0 + lv.split_tokens);
     if (row0 >= rows_b || t0 >= t1)
         return;
 
-    const char* __restrict__ kg = (const char*)p.k_prefix;
-    const char* __restrict__ vg = (const char*)p.v_prefix;
+    const char* __restrict__ kg = (const char*)lv.k;
+    const char* __restrict__ vg = (const char*)lv.v;
     // the page table is read with scalar loads (uniform index, constant address space)
     typedef const __attribute__((address_space(4))) int* const_int_ptr;
-    const const_int_ptr pages = PAGED ? (const_int_ptr)(p.prefix_pages + p.prefix_indptr[b]) : nullptr;
+    const const_int_ptr pages = PAGED ? (const_int_ptr)(lv.pages + lv.indptr[b]) : nullptr;
     // byte strides of a token row and byte offset of token 0 of this KV head
     const long long tok_stride = PAGED ? 256 : (long long)p.Hkv * 256;
-    const long long head_base = PAGED ? (long long)j * 16 * 256 : ((long long)p.prefix_indptr[b] * p.Hkv + j) * 256;
+    const long long head_base = PAGED ? (long long)j * 16 * 256 : ((long long)lv.indptr[b] * p.Hkv + j) * 256;
     const long long page_stride = (long long)p.Hkv * 16 * 256;
 
     // ---- query fragments (B operand): column = this lane's row, k-slot = channels 16 s + 8 h
@@ -436,7 +456,7 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, uint4* lds, int
     const float l = l_run + __shfl_xor(l_run, 32);
     if (!row_ok)
         return;
-    const long long prow = part_index(p, out_row, p.prefix_slot0 + split);
+    const long long prow = part_index(p, out_row, lv.slot0 + split);
     if (h == 0)
         p.part_ml[prow] = make_float2(m_run, l);
     // the split's own normalised output, fp16 (l > 0: a split holds at least one token)

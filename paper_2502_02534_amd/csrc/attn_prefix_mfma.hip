@@ -14,7 +14,7 @@ attn_prefix_mfma_kernel(AttnParams p)
 {
     constexpr int KS = WAVES == 4 ? 2 : 4, VS = WAVES == 4 ? 3 : 4, AHEAD = WAVES == 4 ? 1 : 2;
     __shared__ uint4 lds[prefix_lds_bytes(KS, VS) / 16];
-    prefix_body<WAVES, PAGED, KS, VS, AHEAD>(p, lds, blockIdx.x, blockIdx.y, blockIdx.z);
+    prefix_body<WAVES, PAGED, KS, VS, AHEAD>(p, level_of(p, (int)gridDim.y), lds, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 template <int WAVES>

@@ -26,6 +26,28 @@ struct MergeLevel {
 };
 constexpr int kMaxLevels = 4;
 
+// One level of shared prefixes as the prefix pass sees it.
+struct PrefixLevelParams {
+    const void* k;
+    const void* v;
+    const int* lens;
+    const int* indptr;
+    const int* pages;
+    const int* sample_indptr;
+    int split_tokens;  // tokens per split
+    int num_splits;
+    int slot0;         // first partial-state slot of the level
+    int rowtiles;      // row tiles per (group, KV head) in the launch that carries the level
+    int groups;        // number of groups
+};
+
+// The levels a fused launch carries, with the range of prefix workgroups of each.
+struct FusedLevels {
+    int num_levels;
+    int first_block[kMaxLevels + 1];  // prefix workgroups of level l: first_block[l] .. first_block[l+1]-1
+    PrefixLevelParams level[kMaxLevels];
+};
+
 struct AttnParams {
     int dtype, Hq, Hkv, D, G, B, N, max_spp, page_size;
     float scale_log2;  // sm_scale * log2(e)
@@ -121,6 +143,8 @@ bool suffix_mfma_supported(const AttnParams& p);
 hipError_t launch_attn_suffix_mfma(const AttnParams& p, hipStream_t s);
 bool attn_fused_supported(const AttnParams& p);
 hipError_t launch_attn_fused(const AttnParams& p, hipStream_t s);
+bool attn_fused_levels_supported(const AttnParams& p, const FusedLevels& fl);
+hipError_t launch_attn_fused_levels(const AttnParams& p, const FusedLevels& fl, hipStream_t s);
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
 hipError_t launch_kv_append(const KvAppendParams& a, hipStream_t s);
 size_t sampler_workspace_bytes(long long rows, long long vocab);

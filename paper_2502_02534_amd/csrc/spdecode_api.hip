@@ -302,7 +302,47 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
                                          : (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    // Every level is one prefix pass over its own grouping of the samples.  The level with the most
+    // Several levels, bf16 tiles everywhere: all prefix levels and the suffix pass in one launch.
+    if (num_levels > 1 && stages == (SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE)) {
+        spd::FusedLevels fl;
+        fl.num_levels = 0;
+        long long blocks = 0;
+        fl.first_block[0] = 0;
+        for (int l = 0; l < num_levels; ++l) {
+            if (lp.num_splits[l] <= 0)
+                continue;  // an empty level has nothing to compute
+            const spd_prefix_level& L = levels[l];
+            spd::PrefixLevelParams& lv = fl.level[fl.num_levels];
+            const int spp = L.max_samples_per_group > 0 ? L.max_samples_per_group : desc->num_samples;
+            lv.k = L.k;
+            lv.v = L.v;
+            lv.lens = L.lens;
+            lv.indptr = L.indptr;
+            lv.pages = L.page_indices;
+            lv.sample_indptr = L.sample_indptr;
+            lv.split_tokens = lp.split_tokens[l];
+            lv.num_splits = lp.num_splits[l];
+            lv.slot0 = lp.slot0[l];
+            lv.rowtiles = (spp * p.G + 127) / 128;
+            lv.groups = L.num_groups;
+            blocks += (long long)lv.num_splits * lv.rowtiles * lv.groups * p.Hkv;
+            fl.first_block[++fl.num_levels] = (int)blocks;
+        }
+        for (int l = fl.num_levels + 1; l <= spd::kMaxLevels; ++l)
+            fl.first_block[l] = (int)blocks;
+        bool one_launch = fl.num_levels >= 1 && blocks < 0x7fffffffLL && spd::attn_fused_levels_supported(p, fl);
+#ifdef SPD_TUNING
+        if (getenv("SPD_TUNE_NO_FUSED")) one_launch = false;
+#endif
+        if (one_launch) {
+            if (spd::launch_attn_fused_levels(p, fl, s) != hipSuccess)
+                return SPD_ELAUNCH;
+            if (spd::launch_attn_merge(p, s) != hipSuccess)
+                return SPD_ELAUNCH;
+            return SPD_OK;
+        }
+    }
+    // Otherwise every level is one prefix pass over its own grouping of the samples.  The level with the most
     // tokens shares its launch with the suffix pass (where the fused kernel takes the shape), so
     // that the suffix stream overlaps with as much matrix work as possible; it is launched last.
     int with_suffix = 0;
