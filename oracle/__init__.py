@@ -1,6 +1,6 @@
 """fp64 CPU checker for the decode-step library.  TEST INFRASTRUCTURE ONLY.
 
-Nothing under the product package may import this.  The arithmetic is in the two
+Nothing under the product package may import this.  The arithmetic is in the
 C files next to this one (plain loops, fp64); this module compiles them with
 gcc and hands numpy arrays to them through ctypes.
 """
@@ -15,7 +15,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "liboracle.so")
-_SRCS = [os.path.join(_HERE, f) for f in ("attention_oracle.c", "sampler_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("attention_oracle.c", "sampler_oracle.c", "sampler_filtered_oracle.c")]
 _lib = None
 
 
@@ -35,6 +35,7 @@ def _load():
         _lib = ctypes.CDLL(build())
         _lib.oracle_attention.restype = ctypes.c_int
         _lib.oracle_sample_tokens.restype = ctypes.c_int
+        _lib.oracle_sample_tokens_filtered.restype = ctypes.c_int
     return _lib
 
 
@@ -126,3 +127,33 @@ def sample_tokens(logits, temperature, top_p, uniforms):
     if rc != 0:
         raise ValueError("oracle_sample_tokens: inconsistent arguments")
     return {"token": tok, "cdf_lo": lo, "cdf_hi": hi, "cut_margin": mg, "kept": kept}
+
+
+def sample_tokens_filtered(logits, temperature, top_p, uniforms, top_k=None, min_p=None):
+    """Sampling with min-p, top-k and top-p filters applied in that order, per row, in fp64.
+
+    `top_k` int32 [rows] (0 = off) and `min_p` float32 [rows] (0 = off) may be None.  Returns
+    the dict of `sample_tokens` plus filter_margin float64 [rows] (relative distance between a
+    filter threshold and the nearest probability not exactly on it; inf when no filter acts).
+    """
+    lib = _load()
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    rows, vocab = logits.shape
+    t = np.ascontiguousarray(temperature, dtype=np.float32)
+    tp = np.ascontiguousarray(top_p, dtype=np.float32)
+    u = np.ascontiguousarray(uniforms, dtype=np.float32)
+    tk = None if top_k is None else np.ascontiguousarray(top_k, dtype=np.int32)
+    mp = None if min_p is None else np.ascontiguousarray(min_p, dtype=np.float32)
+    assert t.shape == (rows,) and tp.shape == (rows,) and u.shape == (rows,)
+    tok = np.empty(rows, dtype=np.int32)
+    lo = np.empty(rows, dtype=np.float64)
+    hi = np.empty(rows, dtype=np.float64)
+    mg = np.empty(rows, dtype=np.float64)
+    fm = np.empty(rows, dtype=np.float64)
+    kept = np.empty(rows, dtype=np.int32)
+    rc = lib.oracle_sample_tokens_filtered(_p(logits), ctypes.c_int64(rows), ctypes.c_int64(vocab),
+                                           ctypes.c_int64(vocab), _p(t), _p(tp), _p(tk), _p(mp), _p(u),
+                                           _p(tok), _p(lo), _p(hi), _p(mg), _p(fm), _p(kept))
+    if rc != 0:
+        raise ValueError("oracle_sample_tokens_filtered: inconsistent arguments")
+    return {"token": tok, "cdf_lo": lo, "cdf_hi": hi, "cut_margin": mg, "filter_margin": fm, "kept": kept}
