@@ -212,6 +212,32 @@ SPD_API int sample_tokens(const void *logits, int32_t logits_dtype,
                   void *stream);
 
 /*
+ * sample_tokens with two more filters ahead of top-p (the paper sets only the temperature, App.
+ * "Experiment settings"; min-p and top-k are the usual companions of top-p, and the rule is fixed
+ * here).  Per row, each filter acts on what the previous one kept:
+ *
+ *   p_i = exp((x_i - max x) / T_r), so the most probable token has p = 1
+ *   min-p  (min_p[r] > 0): keep p_i >= min_p[r]
+ *   top-k  (top_k[r] > 0): keep the top_k[r] most probable of those, and every tie with the last
+ *   top-p  over the survivors' mass S2: tau = the largest value t with
+ *          mass{survivors with p_i >= t} >= top_p_r * S2; keep p_i >= tau
+ *   then the walk of sample_tokens over what is left.
+ *
+ *   top_k   int32 [rows] or NULL (= off everywhere); 0 = off for the row
+ *   min_p   float [rows] or NULL; 0 = off for the row; values in (0, 1]
+ * With both NULL this is sample_tokens.  Rows with a filter take a one-workgroup-per-row kernel
+ * that reads the row several times; it is exact, not fast.  Everything else as for sample_tokens.
+ */
+SPD_API int sample_tokens_filtered(const void *logits, int32_t logits_dtype,
+                           int64_t rows, int64_t vocab, int64_t row_stride,
+                           const float *temperature, const float *top_p,
+                           const int32_t *top_k, const float *min_p,
+                           const float *uniforms,
+                           int32_t *tokens_out,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
  * Between two decode steps of the sampling loop (the paper generates up to 1024
  * tokens per sample, App. "Experiment settings"): append one token's K and V to the
  * private suffix of every live sample and add one to its suffix_lens entry, all on

@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.sample_tokens_workspace_size.argtypes = [i64, i64]
     lib.sample_tokens.restype = ctypes.c_int
     lib.sample_tokens.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.sample_tokens_filtered.restype = ctypes.c_int
+    lib.sample_tokens_filtered.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lp = ctypes.POINTER(PrefixLevel)
     lib.shared_prefix_decode_attn_levels_workspace_size.restype = sz
     lib.shared_prefix_decode_attn_levels_workspace_size.argtypes = [dp, ctypes.c_int32, lp, i64]
@@ -178,3 +180,13 @@ def shared_prefix_decode_attn_levels(desc: AttnDesc, q, levels, k_suffix, v_suff
         _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "shared_prefix_decode_attn_levels")
+
+
+def sample_tokens_filtered(logits, logits_dtype: int, rows: int, vocab: int, row_stride: int, temperature,
+                           top_p, top_k, min_p, uniforms, tokens_out, workspace, stream=None) -> None:
+    rc = load().sample_tokens_filtered(
+        _ptr(logits), logits_dtype, int(rows), int(vocab), int(row_stride), _ptr(temperature), _ptr(top_p),
+        _ptr(top_k), _ptr(min_p), _ptr(uniforms), _ptr(tokens_out), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "sample_tokens_filtered")

@@ -205,71 +205,68 @@ __device__ void sample_row_from_memory(const SamplerParams& sp, long long r, Row
         rs.c_lo = (float)(c - (double)rs.c_hi);
     }
 
-    // ---- pass 2: total mass and top-level histogram -------------------------------------
-    for (int b = tid; b < kBins; b += kBlock)
-        hist[b] = 0.0;
-    __syncthreads();
+    // ---- filters ahead of the nucleus: a lower bound `lb_bits` on the bit pattern of p ----------
+    // (p > 0, so patterns order like values.)  min-p: p >= min_p, and the maximum has p = 1.
+    // top-k: the k-th largest pattern among what min-p left, found by radix select on counts;
+    // every tie with it is kept.
     const float top_p = sp.top_p[r];
     const bool cut = top_p < 1.f;
+    const float min_p = sp.min_p ? sp.min_p[r] : 0.f;
+    const int top_k = sp.top_k ? sp.top_k[r] : 0;
+    uint32_t lb_bits = min_p > 0.f ? __float_as_uint(min_p) : 0u;
+
+    // Radix select over the patterns >= lb (bits 30..20, 19..9, 8..0): the highest pattern whose
+    // upper set reaches `need`, counting tokens (`by_count`) or summing their probabilities.
+    auto select = [&](bool by_count, double need, uint32_t lb) -> uint32_t {
+        uint32_t prefix = 0u;
+        double above = 0.0;
+        for (int level = 0; level < 3; ++level) {
+            const int shift = level == 0 ? 20 : level == 1 ? 9 : 0;
+            const int bits = level == 2 ? 9 : 11;
+            for (int b = tid; b < kBins; b += kBlock)
+                hist[b] = 0.0;
+            __syncthreads();
+            for (int i = tid; i < V; i += kBlock) {
+                const float pv = prob(x[i], rs);
+                const uint32_t u = __float_as_uint(pv) & 0x7fffffffu;
+                if (u >= lb && (level == 0 || (u >> (shift + bits)) == prefix))
+                    atomicAdd(&hist[(u >> shift) & ((1u << bits) - 1u)], by_count ? 1.0 : (double)pv);
+            }
+            __syncthreads();
+            pick_bin(hist, above, need, &sh_bin, &sh_low, &sh_above, scratch);
+            prefix = (prefix << bits) | (uint32_t)sh_bin;
+            above = sh_above;
+            __syncthreads();
+        }
+        return prefix;
+    };
+    if (top_k > 0)
+        lb_bits = max(lb_bits, select(true, (double)top_k, lb_bits));
+
+    // ---- pass 2: mass of what the filters left; nucleus threshold among it --------------------------
     double part = 0.0;
     {
         float acc = 0.f;
         int cnt = 0;
         for (int i = tid; i < V; i += kBlock) {
             const float pv = prob(x[i], rs);
+            if ((__float_as_uint(pv) & 0x7fffffffu) < lb_bits)
+                continue;
             acc += pv;
             if (++cnt == 32) {  // bound the fp32 run length before widening
                 part += (double)acc;
                 acc = 0.f;
                 cnt = 0;
             }
-            if (cut)
-                atomicAdd(&hist[(__float_as_uint(pv) >> 20) & 0x7ffu], (double)pv);
         }
         part += (double)acc;
     }
     const double S = block_sum_f64(part, scratch);
 
-    uint32_t tau_bits = 0u;  // keep everything
+    uint32_t tau_bits = lb_bits;  // keep everything the filters left
     double Z = S;
-    if (cut) {
-        const double need = (double)top_p * S;
-        // level 1: bits 30..20
-        pick_bin(hist, 0.0, need, &sh_bin, &sh_low, &sh_above, scratch);
-        const uint32_t b1 = (uint32_t)sh_bin;
-        double above = sh_above;
-        __syncthreads();
-        // level 2: bits 19..9 of the patterns that share b1
-        for (int b = tid; b < kBins; b += kBlock)
-            hist[b] = 0.0;
-        __syncthreads();
-        for (int i = tid; i < V; i += kBlock) {
-            const float pv = prob(x[i], rs);
-            const uint32_t u = __float_as_uint(pv) & 0x7fffffffu;
-            if ((u >> 20) == b1)
-                atomicAdd(&hist[(u >> 9) & 0x7ffu], (double)pv);
-        }
-        __syncthreads();
-        pick_bin(hist, above, need, &sh_bin, &sh_low, &sh_above, scratch);
-        const uint32_t b2 = (uint32_t)sh_bin;
-        above = sh_above;
-        __syncthreads();
-        // level 3: bits 8..0
-        for (int b = tid; b < kBins; b += kBlock)
-            hist[b] = 0.0;
-        __syncthreads();
-        const uint32_t prefix = (b1 << 11) | b2;
-        for (int i = tid; i < V; i += kBlock) {
-            const float pv = prob(x[i], rs);
-            const uint32_t u = __float_as_uint(pv) & 0x7fffffffu;
-            if ((u >> 9) == prefix)
-                atomicAdd(&hist[u & 0x1ffu], (double)pv);
-        }
-        __syncthreads();
-        pick_bin(hist, above, need, &sh_bin, &sh_low, &sh_above, scratch);
-        tau_bits = (prefix << 9) | (uint32_t)sh_bin;
-        __syncthreads();
-    }
+    if (cut)
+        tau_bits = max(lb_bits, select(false, (double)top_p * S, lb_bits));
 
     // ---- pass 3: kept mass per 256-element segment, in vocabulary order -----------------
     const int num_tiles = (V + kTile - 1) / kTile;
@@ -1335,7 +1332,7 @@ hipError_t launch_sampler(const SamplerParams& p, void* ws, hipStream_t s)
 {
     const int slices = sampler_slices(p.rows, p.vocab);
     const bool aligned = (p.stride % 4 == 0) && ((uintptr_t)p.logits % 16 == 0);
-    if (slices == 0 || !aligned || p.vocab < 4) {
+    if (slices == 0 || !aligned || p.vocab < 4 || p.top_k || p.min_p) {  // filters: whole-row kernel only
         hipLaunchKernelGGL(sample_rows_kernel, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p);
         return hipGetLastError();
     }

@@ -101,6 +101,8 @@ struct SamplerParams {
     const float* top_p;
     const float* uniforms;
     int* tokens;
+    const int* top_k;    // per row, 0 = off; may be null
+    const float* min_p;  // per row, 0 = off; may be null
 };
 
 // Index of the partial state of output row `row` (= n * Hq + h) in slot `slot`.

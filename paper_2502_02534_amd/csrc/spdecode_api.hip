@@ -481,6 +481,15 @@ int sample_tokens(const void* logits, int32_t logits_dtype, int64_t rows, int64_
                   const float* uniforms, int32_t* tokens_out, void* workspace,
                   size_t workspace_bytes, void* stream)
 {
+    return sample_tokens_filtered(logits, logits_dtype, rows, vocab, row_stride, temperature, top_p, nullptr,
+                                  nullptr, uniforms, tokens_out, workspace, workspace_bytes, stream);
+}
+
+int sample_tokens_filtered(const void* logits, int32_t logits_dtype, int64_t rows, int64_t vocab,
+                           int64_t row_stride, const float* temperature, const float* top_p,
+                           const int32_t* top_k, const float* min_p, const float* uniforms,
+                           int32_t* tokens_out, void* workspace, size_t workspace_bytes, void* stream)
+{
     if (!logits || !temperature || !top_p || !uniforms || !tokens_out)
         return SPD_EINVAL;
     if (rows <= 0 || vocab <= 0 || row_stride < vocab || rows > 0x7fffffffll)
@@ -502,6 +511,8 @@ int sample_tokens(const void* logits, int32_t logits_dtype, int64_t rows, int64_
     p.top_p = top_p;
     p.uniforms = uniforms;
     p.tokens = tokens_out;
+    p.top_k = top_k;
+    p.min_p = min_p;
     if (spd::launch_sampler(p, workspace, (hipStream_t)stream) != hipSuccess)
         return SPD_ELAUNCH;
     return SPD_OK;
