@@ -30,9 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # machine).  Keyed by (kernel, workload); anything not listed is reported as null.  The entry
 # must be dropped when the kernel changes.  Source: profiles/hbm_traffic_cfg3_pmc.txt
 TRAFFIC_BYTES = {
-    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95240.1 * 2.0 + 11355.8) * 1024),
+    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95247.5 * 2.0 + 11340.6) * 1024),
     ("prefix", "cfg3-bf16-p8192-n64"): int((18532.4 * 2.0 + 9216.0) * 1024),
-    ("suffix", "cfg3-bf16-p8192-n64"): int((77083.3 * 2.0 + 2064.5) * 1024),
+    ("suffix", "cfg3-bf16-p8192-n64"): int((77084.4 * 2.0 + 2064.0) * 1024),
 }
 
 
