@@ -141,10 +141,9 @@ def main() -> int:
 
     it = args.kernel_iters
     # A step runs the prefix and the suffix pass in one launch when the library's fused kernel takes
-    # the shape (bf16, head_dim 128, more than 64 query rows per KV head, group size <= 16); the
+    # the shape (bf16, head_dim 128, group size <= 16); the
     # two passes are also timed as launches of their own for their separate rooflines.
-    max_rows = int(max(first.sample_indptr[b + 1] - first.sample_indptr[b] for b in range(sp.num_prompts))) * sp.group
-    fused = sp.dtype == "bf16" and sp.head_dim == 128 and max_rows > 64 and sp.group <= 16 and suffix_bytes > 0
+    fused = sp.dtype == "bf16" and sp.head_dim == 128 and sp.group <= 16 and suffix_bytes > 0
     us = {
         "attn_fused": time_stage(attn_stage(B.STAGE_PREFIX | B.STAGE_SUFFIX), it),
         "prefix": time_stage(attn_stage(B.STAGE_PREFIX), it),

@@ -1,4 +1,4 @@
-// Prefix and suffix pass in one launch (bf16, head_dim 128, more than 64 query rows per KV head).
+// Prefix and suffix pass in one launch (bf16, head_dim 128).
 //
 // The prefix pass is bound by the matrix pipe and the vector ALU, the suffix pass by HBM, and
 // neither needs the other's result before the merge.  One grid of 256-thread workgroups with

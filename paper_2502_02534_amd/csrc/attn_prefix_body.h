@@ -2,8 +2,8 @@
 // a dense row tile against the shared prompt KV, so the prompt is read once per row
 // tile instead of once per sample.
 //
-// Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix); WAVES is 2,
-// 4 or 8.
+// Workgroup = (prompt b, KV head j, tile of 32*WAVES query rows, split of the prefix); WAVES is 4
+// or 8.
 // A query row is (sample, head in group); each wavefront owns 32 rows (one 32-wide column
 // block of the transposed products).
 //

@@ -7,7 +7,7 @@ namespace {
 using namespace prefix_impl;
 
 // 128-row workgroups (4 wavefronts) take the short rings (80 KB) so that two of them share a CU;
-// the others (2 or 8 wavefronts) keep the long rings, copies two tiles ahead.
+// 256-row workgroups (8 wavefronts) keep the long rings, copies two tiles ahead.
 template <int WAVES, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES == 4 ? 2 : 1, 2))) void
 attn_prefix_mfma_kernel(AttnParams p)
@@ -38,30 +38,27 @@ bool prefix_mfma_supported(const AttnParams& p)
            (p.page_size == 0 || p.page_size == 16) && (long long)p.B * p.Hkv <= 65535;
 }
 
-// Rows per workgroup that the split plan and the fused launch assume for a problem with `rows` query
-// rows per (prompt, KV head): 32 rows per wavefront, 2 or 4 wavefronts.  (Workgroups of 8 wavefronts
-// and 256 rows are slower as soon as the pass shares a launch with the suffix pass: a 4-wavefront
-// workgroup leaves room on its CU for a suffix workgroup.)
-int prefix_mfma_block_rows(int rows)
+// Rows per workgroup that the split plan and the fused launch assume: 128 (four wavefronts of 32
+// rows) whatever the row count.  Workgroups of 8 wavefronts and 256 rows are slower as soon as the
+// pass shares a launch with the suffix pass (a 4-wavefront workgroup leaves room on its CU for a
+// suffix workgroup), and smaller ones (64 rows, 128 threads) gained nothing even for a handful of
+// rows, where the pass is bound by latency, not by the idle wavefronts.
+int prefix_mfma_block_rows(int)
 {
-    return rows > 64 ? 128 : 64;
+    return 128;
 }
 
 hipError_t launch_attn_prefix_mfma(const AttnParams& p, hipStream_t s)
 {
     if (p.num_prefix_splits <= 0)
         return hipSuccess;
-    if (prefix_mfma_block_rows(p.max_spp * p.G) == 128) {
-        // On its own (no suffix workgroups to share a CU with) a matrix-bound pass does better with
-        // 256-row workgroups and the long rings, provided that still gives most CUs a workgroup;
-        // the split plan does not depend on the row tile.
-        const long long wide_blocks =
-            (long long)p.num_prefix_splits * ((p.max_spp * p.G + 255) / 256) * p.B * p.Hkv;
-        if (p.max_spp * p.G > 128 && wide_blocks >= 192)
-            return launch_waves<8>(p, s);
-        return launch_waves<4>(p, s);
-    }
-    return launch_waves<2>(p, s);
+    // On its own (no suffix workgroups to share a CU with) a matrix-bound pass does better with
+    // 256-row workgroups and the long rings, provided that still gives most CUs a workgroup;
+    // the split plan does not depend on the row tile.
+    const long long wide_blocks = (long long)p.num_prefix_splits * ((p.max_spp * p.G + 255) / 256) * p.B * p.Hkv;
+    if (p.max_spp * p.G > 128 && wide_blocks >= 192)
+        return launch_waves<8>(p, s);
+    return launch_waves<4>(p, s);
 }
 
 }  // namespace spd
