@@ -269,14 +269,15 @@ def main() -> int:
         ncores = os.cpu_count() or 1
         env_threads = int(os.environ.get("OMP_NUM_THREADS", ncores))
         total_rows = sp.num_samples * sp.num_q_heads
-        # bounded sample: at most 256 attention rows of one layer and 32 sampler rows, scaled up
+        # bounded sample: at most 4096 attention rows of one layer and 128 sampler rows, scaled up
+        # (configuration 3 fits whole: about ten core-seconds)
         rows = np.arange(total_rows, dtype=np.int64)
-        if total_rows > 256:
-            rows = np.linspace(0, total_rows - 1, 256).astype(np.int64)
+        if total_rows > 4096:
+            rows = np.linspace(0, total_rows - 1, 4096).astype(np.int64)
         t0 = time.perf_counter()
         oracle.attention_inputs(first, rows=rows)
         t_attn = (time.perf_counter() - t0) * (total_rows / len(rows)) * sp.layers
-        srows = min(32, sin.logits.shape[0])
+        srows = min(128, sin.logits.shape[0])
         t0 = time.perf_counter()
         oracle.sample_tokens(sin.logits[:srows], sin.temperature[:srows], sin.top_p[:srows], sin.uniforms[:srows])
         t_samp = (time.perf_counter() - t0) * (sin.logits.shape[0] / srows)
