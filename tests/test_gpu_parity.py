@@ -110,6 +110,10 @@ RAGGED = [
          prefix_len=(64, 129), suffix_len=(1, 33)),
     dict(dtype="bf16", num_q_heads=16, num_kv_heads=2, head_dim=128, num_prompts=1, samples_per_prompt=24,
          prefix_len=(2049, 2049), suffix_len=(0, 0)),
+    # more prefix workgroups than CUs (6 prompts x 8 KV heads x 2 row tiles x 3 splits = 288): the fused
+    # launch spreads them through the grid
+    dict(dtype="bf16", num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=6, samples_per_prompt=40,
+         prefix_len=(600, 900), suffix_len=(0, 150)),
 ]
 
 
