@@ -251,6 +251,30 @@ def main() -> int:
                              "on the device, lengths on the device; graph = one captured step replayed"}
         del lp, gl, graph, q_s, k_s, v_s, u_s
 
+    # ---- the small configuration next to the main one: whole-step rate only -------------------------
+    also = {}
+    if args.config == 3:
+        sp2 = workloads.SPECS[2]
+        lay2 = [device.upload_attn(workloads.make_attn_inputs(2)) for _ in range(4)]
+        smp2 = [device.upload_sampler(workloads.make_sampler_inputs(2)) for _ in range(4)]
+
+        def step2(i):
+            lay2[i % 4].run()
+            smp2[i % 4].run()
+
+        for i in range(20):
+            step2(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(400):
+            step2(i)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) / 400 * 1e3
+        also[sp2.name] = {"value": 1e3 / ms2, "unit": "steps/s", "ms_per_step": ms2,
+                          "tokens_per_sec": sp2.num_samples * 1e3 / ms2,
+                          "note": "16 samples, 2048-token prompt: launch-latency bound (about 10 MB per step)"}
+        del lay2, smp2
+
     if args.calibrate_copy:
         # a plain elementwise kernel of known size in the same process: 256 MiB read and 256 MiB
         # written per call (torch's out-of-place multiply; a tensor copy would go to the runtime's
@@ -299,7 +323,7 @@ def main() -> int:
         "tokens_per_sec": sp.num_samples * 1e3 / ms_per_step,
         "step_algorithmic_bytes": step_bytes,
         "step_GBps": step_bytes / ms_per_step / 1e6,
-        "roofline": roofline, "kernels": kernels, "decode_loop": loop_info, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "decode_loop": loop_info, "also": also, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     return 0
