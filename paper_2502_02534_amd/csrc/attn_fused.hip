@@ -11,9 +11,12 @@
 // streams, HBM is busy during the prefix pass, and there is no launch (with its ramp and tail)
 // between the two passes.  Both bodies are the ones the separate kernels use.
 //
+// The kernel takes a table of prefix levels (a tree of shared prefixes has several; the plain call
+// has one), each with its own range of prefix workgroups.
+//
 // Measured alternatives: 512-thread workgroups with 128 KB (one workgroup per CU, so prefix and
 // suffix wavefronts never share a CU) 9 to 15 % slower; spreading the two roles evenly over the
-// grid instead of prefix-first another 4 to 10 % slower.
+// grid although the prefix workgroups fit one per CU another 4 to 10 % slower.
 #include "attn_prefix_body.h"
 #include "attn_suffix_body.h"
 

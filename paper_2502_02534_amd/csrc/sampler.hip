@@ -1,10 +1,11 @@
 // Temperature / nucleus / inverse-CDF token sampler.
 //
-// Two paths.  The sliced path (below, two stream-ordered kernels) reads a row from HBM once,
-// takes a second look that caches serve when the logits fit, and finds the exact nucleus
-// threshold without sorting.  The whole-row routine (one workgroup per row, every pass from
-// memory) covers rows the sliced path does not take: unaligned rows, vocabularies beyond
-// 16 slices, and the rare row whose candidate set overflows.
+// Two paths.  The sliced path (below: two stream-ordered kernels, four for launches with many
+// workgroups) reads a row from HBM once, takes a second look that caches serve when the logits
+// fit, and finds the exact nucleus threshold without sorting.  The whole-row routine (one
+// workgroup per row, every pass from memory) covers what the sliced path does not take: unaligned
+// rows, vocabularies beyond 16 slices, the rare row whose candidate set overflows, and rows with
+// a min-p or top-k filter.
 //
 // Probabilities are evaluated by one shared routine, p_i = 2^((x_i - max) c) with
 // c = log2(e)/T carried as hi + lo floats, so every pass sees the same bits; every sum that
