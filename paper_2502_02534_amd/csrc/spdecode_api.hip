@@ -62,7 +62,7 @@ int plan_prefix_split(const spd_attn_desc* d, int groups, int spp, long long max
         if (want > max_splits) want = max_splits;
         long long t = (max_prefix + want - 1) / want;
         t = (t + 63) / 64 * 64;
-        if (t < 64) t = 64;
+        if (t < 128) t = 128;  // at least two tiles per split: a one-tile workgroup is all start-up
         split = (int)t;
     } else {
         split = part_tokens(max_prefix, 256, max_splits, 64);
