@@ -109,3 +109,26 @@ def test_config5_attention_sampled_rows(dev, oracle):
 def test_config5_sampler_every_row(dev, oracle):
     print("config 5 sampler (1024 rows, per-prompt temperatures)", flush=True)
     _tokens(dev, oracle, W.make_sampler_inputs(5))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(num_q_heads=32, num_kv_heads=8, num_prompts=1, samples_per_prompt=3, prefix_len=(300001, 300001),
+         suffix_len=(70000, 90000)),
+    dict(num_q_heads=16, num_kv_heads=2, num_prompts=2, samples_per_prompt=5, prefix_len=(100000, 200000),
+         suffix_len=(0, 50000), page_size=16),
+])
+def test_very_long_sequences(dev, oracle, kw):
+    """Hundreds of thousands of tokens per sequence (64 prefix splits, 61-64 suffix chunks, byte offsets
+    beyond 32 bits), on rows the checker computes one by one."""
+    print(f"long sequences: {kw}", flush=True)
+    inp = W.make_attn_inputs(0, spec=W.small_spec(**kw), seed=77)
+    d = dev.upload_attn(inp)
+    d.out.fill_(float("nan"))
+    d.run()
+    torch.cuda.synchronize()
+    rows = np.arange(0, inp.q.shape[0] * inp.q.shape[1], 7)
+    ref, ref_lse = oracle.attention_inputs(inp, rows=rows)
+    got = d.out.float().cpu().numpy().astype(np.float64).reshape(-1, inp.q.shape[2])[rows]
+    lse = d.lse.cpu().numpy().astype(np.float64).reshape(-1)[rows]
+    assert np.abs(got - ref).max() <= 2e-2
+    assert np.abs(lse - ref_lse).max() <= 2e-3
