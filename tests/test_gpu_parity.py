@@ -161,6 +161,8 @@ SAMPLER_CASES = [
     dict(rows=8, vocab=128256, sigma=3, T=0.2, top_p=0.5),
     dict(rows=8, vocab=1000, sigma=0, T=1.0, top_p=0.9),           # all logits equal
     dict(rows=8, vocab=1000, sigma=3, T=1.0, top_p=1e-6),          # nucleus = argmax only
+    dict(rows=4, vocab=262144, sigma=3, T=0.9, top_p=0.92),        # the largest vocabulary the call takes (16 slices)
+    dict(rows=3, vocab=200003, sigma=3, T=1.1, top_p=0.97),        # 13 slices and a 3-logit tail
 ]
 
 
