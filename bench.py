@@ -30,9 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # machine).  Keyed by (kernel, workload); anything not listed is reported as null.  The entry
 # must be dropped when the kernel changes.  Source: profiles/hbm_traffic_cfg3_pmc.txt
 TRAFFIC_BYTES = {
-    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95247.5 * 2.0 + 11340.6) * 1024),
-    ("prefix", "cfg3-bf16-p8192-n64"): int((18532.4 * 2.0 + 9216.0) * 1024),
-    ("suffix", "cfg3-bf16-p8192-n64"): int((77084.4 * 2.0 + 2064.0) * 1024),
+    ("attn_fused", "cfg3-bf16-p8192-n64"): int((95249.2 * 2.0 + 11341.9) * 1024),
+    ("prefix", "cfg3-bf16-p8192-n64"): int((18536.9 * 2.0 + 9216.0) * 1024),
+    ("suffix", "cfg3-bf16-p8192-n64"): int((77085.8 * 2.0 + 2064.5) * 1024),
 }
 
 
@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--loop-steps", type=int, default=48,
                     help="decode steps of the append + attention + sampler loop timed eagerly and as a "
                          "replayed graph (0 = skip; single-layer workloads only)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the small configuration measured beside the main one (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -253,7 +255,7 @@ def main() -> int:
 
     # ---- the small configuration next to the main one: whole-step rate only -------------------------
     also = {}
-    if args.config == 3:
+    if args.config == 3 and not args.no_also:
         sp2 = workloads.SPECS[2]
         lay2 = [device.upload_attn(workloads.make_attn_inputs(2)) for _ in range(4)]
         smp2 = [device.upload_sampler(workloads.make_sampler_inputs(2)) for _ in range(4)]
