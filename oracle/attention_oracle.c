@@ -22,8 +22,9 @@
  * Parity pins (tests/test_oracle_attention.py): brute-force numpy softmax on
  * tiny odd shapes, uniform keys => mean of the value rows, a dominant key, score
  * shift invariance, constant-V-per-KV-head (head mapping), token/page
- * permutation invariance, the paper's serial MaxSum recurrence, and the
- * two-part log-sum-exp merge identity.
+ * permutation invariance, the running (max, sum, accumulator) state of the
+ * paper's attention tasks stated from its definition on growing key sets, and
+ * the log-sum-exp merge identity on block-wise splits.
  */
 #include <math.h>
 #include <stdint.h>

@@ -960,6 +960,14 @@ __device__ __forceinline__ void finish_row(SelectLds& L, const SamplerParams& sp
         }
     }
     __syncthreads();
+    if (!cut) {
+        // Nothing is cut: the normaliser is the sum of the segments as they stand now, i.e. with the
+        // row's last one to three logits (which travel as candidates) included.
+        double part = 0.0;
+        for (int sidx = tid; sidx < nseg; sidx += kBlock)
+            part += seg_mass[sidx];
+        Z = block_sum_f64(part, L.row.scratch);
+    }
     const double target = (double)sp.uniforms[r] * Z;
 
     if (wave == 0) {

@@ -4,6 +4,7 @@ a probability that fp32 and fp64 may order differently."""
 import numpy as np
 import pytest
 
+from gpu_checks import compare_tokens
 from paper_2502_02534_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -35,14 +36,8 @@ def _run(dev, x, T, top_p, top_k, min_p, u):
 def _check(dev, oracle, x, T, top_p, top_k, min_p, u):
     tok = _run(dev, x, T, top_p, top_k, min_p, u)
     o = oracle.sample_tokens_filtered(x, T, top_p, u, top_k, min_p)
-    uu = u.astype(np.float64)
-    near = ((np.minimum(np.abs(uu - o["cdf_lo"]), np.abs(uu - o["cdf_hi"])) < 1e-6)
-            | (o["cut_margin"] < 1e-6) | (o["filter_margin"] < 1e-6))
-    bad = (tok != o["token"]) & ~near
-    assert not bad.any(), (np.nonzero(bad)[0][:8], tok[bad][:8], o["token"][bad][:8])
-    assert np.all((tok >= 0) & (tok < x.shape[1]))
-    print(f"  exempt rows {int(near.sum())}, differing tokens {int((tok != o['token']).sum())}, "
-          f"kept min/median/max {o['kept'].min()}/{int(np.median(o['kept']))}/{o['kept'].max()}")
+    compare_tokens(tok, o, u, x.shape[1])
+    print(f"  kept min/median/max {o['kept'].min()}/{int(np.median(o['kept']))}/{o['kept'].max()}")
 
 
 CASES = [

@@ -1,7 +1,7 @@
 """Pins for the fp64 attention checker: it is compared with things other than
-itself: a numpy one-liner, closed forms, invariants, and the serial recurrence
-the paper prints for its attention tasks (App., attn task 0 `MaxSum`; attn task 2
-deferred division)."""
+itself: a numpy one-liner, closed forms, invariants, and the running-state algebra of
+the paper's attention tasks (App., attn tasks 0-2) stated from the definition: the state
+after any set of keys, on growing prefixes and under block-wise merges."""
 import math
 
 import numpy as np
@@ -193,34 +193,20 @@ def test_paged_equals_contiguous_and_ignores_page_order(oracle):
     np.testing.assert_allclose(out_q, out_c, atol=1e-13)
 
 
-# ---- the recurrences printed in the paper, restated here in fp64 -------------------------------
+# ---- partial softmax states and their merge, written from the definition -----------------------
+# The paper's attention tasks (App., attn tasks 0-2) carry a running (maximum, sum, accumulator)
+# state along the keys.  What such a state must hold after any set of keys follows from the plain
+# definition alone, so it is written here as that definition (vectorised, no recurrence): the
+# checker is then compared with it on growing prefixes and on block-wise merges.
 
-def _maxsum_serial(scores, values):
-    """State (m, l, o) updated one (score, value row) at a time, dividing at every step
-    (App., attn task 0, `MaxSum`; initial state (-inf, 0, 0))."""
-    m, l, o = -math.inf, 0.0, np.zeros(values.shape[1])
-    for s, v in zip(scores, values):
-        m_new = max(m, s)
-        l_old = math.exp(m - m_new) * l if l > 0 else 0.0
-        p = math.exp(s - m_new)
-        l_new = p + l_old
-        o = (l_old * o + p * v) / l_new
-        m, l = m_new, l_new
-    return m, l, o
-
-
-def _deferred_division(scores, values):
-    """Running sums rescaled by exp(delta m), one division at the end
-    (App., attn task 2: `ExpMaxDiff`, `WeightedSumSingle`, `WeightedSumDouble`, `Div`)."""
-    m, r, acc = -math.inf, 0.0, np.zeros(values.shape[1])
-    for s, v in zip(scores, values):
-        m_new = max(m, s)
-        d = math.exp(m - m_new) if m > -math.inf else 0.0
-        e = math.exp(s - m_new)
-        r = r * d + e
-        acc = acc * d + e * v
-        m = m_new
-    return m, r, acc
+def _state(scores, values):
+    """(m, l, acc) of a set of keys: m = max s, l = sum exp(s - m), acc = exp(s - m) @ V.
+    The empty set gives (-inf, 0, 0)."""
+    if len(scores) == 0:
+        return -math.inf, 0.0, np.zeros(values.shape[1])
+    m = float(np.max(scores))
+    w = np.exp(scores - m)
+    return m, float(w.sum()), w @ values
 
 
 def _merge(a, b):
@@ -245,20 +231,26 @@ def _scores_values(inp, n, h):
     return K @ q / math.sqrt(sp.head_dim), V, Lp
 
 
-def test_paper_recurrences_equal_the_plain_definition(oracle):
+def test_growing_prefixes_follow_the_state_definition(oracle):
+    """After t keys the result is acc_t / l_t and the log-sum-exp m_t + ln l_t of the state over the
+    first t keys, for every t: the checker run on truncated suffixes against numpy on the same
+    truncation (which is what a token-by-token running state has to reproduce at every step)."""
     sp = W.small_spec(dtype="f32", num_q_heads=4, num_kv_heads=2, head_dim=11, samples_per_prompt=3,
-                      prefix_len=(23, 23), suffix_len=(1, 9))
+                      prefix_len=(23, 23), suffix_len=(9, 9))
     inp = W.make_attn_inputs(0, spec=sp, seed=8)
-    out, lse = oracle.attention_inputs(inp)
-    for n in range(3):
-        for h in range(4):
-            s, V, _ = _scores_values(inp, n, h)
-            m, l, o = _maxsum_serial(s, V)
-            np.testing.assert_allclose(o, out[n, h], atol=1e-12)
-            assert abs(m + math.log(l) - lse[n, h]) < 1e-12
-            m2, r2, acc2 = _deferred_division(s, V)
-            np.testing.assert_allclose(acc2 / r2, out[n, h], atol=1e-12)
-            assert abs(m2 + math.log(r2) - lse[n, h]) < 1e-12
+    import copy
+    for t in range(0, 10):
+        cut = copy.copy(inp)
+        cut.suffix_lens = np.full(3, t, np.int32)
+        out, lse = oracle.attention_inputs(cut)
+        for n in range(3):
+            for h in range(4):
+                s, V, _ = _scores_values(cut, n, h)
+                m, l, acc = _state(s, V)
+                np.testing.assert_allclose(acc / l, out[n, h], atol=1e-12)
+                assert abs(m + math.log(l) - lse[n, h]) < 1e-12
+                p = np.exp(s - s.max())
+                np.testing.assert_allclose((p / p.sum()) @ V, out[n, h], atol=1e-12)
 
 
 def test_cascade_merge_equals_attention_over_concatenation(oracle):
@@ -270,16 +262,16 @@ def test_cascade_merge_equals_attention_over_concatenation(oracle):
     for n in range(4):
         for h in range(4):
             s, V, Lp = _scores_values(inp, n, h)
-            pre = _deferred_division(s[:Lp], V[:Lp])
-            suf = _deferred_division(s[Lp:], V[Lp:])
+            pre = _state(s[:Lp], V[:Lp])
+            suf = _state(s[Lp:], V[Lp:])
             for a, b in ((pre, suf), (suf, pre)):                      # commutative
                 m, l, acc = _merge(a, b)
                 np.testing.assert_allclose(acc / l, out[n, h], atol=1e-12)
                 assert abs(m + math.log(l) - lse[n, h]) < 1e-12
             # any split point of the prefix, merged in any grouping (associative)
             for cut in (1, 16, 36):
-                p1 = _deferred_division(s[:cut], V[:cut])
-                p2 = _deferred_division(s[cut:Lp], V[cut:Lp])
+                p1 = _state(s[:cut], V[:cut])
+                p2 = _state(s[cut:Lp], V[cut:Lp])
                 left = _merge(_merge(p1, p2), suf)
                 right = _merge(p1, _merge(p2, suf))
                 for m, l, acc in (left, right):

@@ -86,37 +86,22 @@ def test_stratified_uniforms_reproduce_the_distribution(oracle):
 
 
 def _threshold_formulation(x, T, top_p, u):
-    """No sort of the whole row: tau = largest distinct p whose tail mass {p_i >= tau} reaches
-    top_p * S minus... found by scanning distinct values; then the index-order walk."""
+    """The rule written without ordering the row: tau is the largest value t among the p_i whose
+    upper set {p_i >= t} has mass >= top_p * S (each upper-set mass is a masked sum over the
+    vocabulary, distinct values visited in no particular order); then the index-order walk."""
     x = np.asarray(x, np.float32).astype(np.float64)
     T, top_p, u = (float(np.float32(v)) for v in (T, top_p, u))
     p = np.exp((x - x.max()) / T)
-    S = 0.0
-    for v in p:
-        S += v
+    S = float(p.sum())
     tau = 0.0
     if top_p < 1.0:
-        # mass strictly above a candidate value v, summed in (p desc, index asc) order like the rule says
-        order = sorted(range(len(p)), key=lambda i: (-p[i], i))
-        c = 0.0
-        tau = p[order[-1]]
-        for i in order:
-            c += p[i]
-            if c >= top_p * S:
-                tau = p[i]
-                break
-    c, Z = 0.0, 0.0
-    for v in p:
-        if v >= tau:
-            Z += v
-    last = -1
-    for i, v in enumerate(p):
-        if v >= tau:
-            last = i
-            c += v
-            if c > u * Z:
-                return i
-    return last
+        reaching = [t for t in set(p.tolist()) if float(np.where(p >= t, p, 0.0).sum()) >= top_p * S]
+        tau = max(reaching) if reaching else float(p.min())
+    kept = p >= tau
+    Z = float(np.where(kept, p, 0.0).sum())
+    running = np.cumsum(np.where(kept, p, 0.0))
+    hit = np.nonzero(kept & (running > u * Z))[0]
+    return int(hit[0]) if len(hit) else int(np.nonzero(kept)[0][-1])
 
 
 def test_second_formulation_agrees_on_random_tiny_rows(oracle):

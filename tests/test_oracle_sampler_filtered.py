@@ -131,3 +131,70 @@ def test_brute_force_on_tiny_vocabularies(oracle):
         got = _one(oracle, x, T, tp, u, top_k=k, min_p=mp)
         want = _brute(x, T, tp, np.float32(u), k, np.float32(mp) if mp else 0.0)
         assert got == want, (trial, x, T, tp, k, mp, u, got, want)
+
+
+def _full(oracle, x, T, top_p, u, top_k=0, min_p=0.0):
+    x = np.asarray([x], dtype=np.float32)
+    r = oracle.sample_tokens_filtered(x, np.float32([T]), np.float32([top_p]), np.float32([u]),
+                                      np.int32([top_k]), np.float32([min_p]))
+    return {k: v[0] for k, v in r.items()}
+
+
+def f32(v):
+    """The value the checker sees for a float32 parameter."""
+    return float(np.float32(v))
+
+
+def test_margins_closed_forms(oracle):
+    """The margins decide which rows a GPU parity test may exempt, so they are pinned to closed
+    forms on the four-token row p = 1/2, 1, 1/8, 1/4 (vocabulary order): a margin stuck at 0, at
+    inf, or measured against the wrong neighbour fails here."""
+    x = np.log(np.float64([4.0, 8.0, 1.0, 2.0]))
+    # no filter acts: nothing to be near to
+    r = _full(oracle, x, 1.0, 1.0, 0.5)
+    assert np.isinf(r["filter_margin"]) and np.isinf(r["cut_margin"])
+    # top_k >= the number of tokens removes nothing either
+    assert np.isinf(_full(oracle, x, 1.0, 1.0, 0.5, top_k=4)["filter_margin"])
+    # min_p = 0.24: the nearest probability is 1/4 -> |0.25 - 0.24| / 0.24
+    r = _full(oracle, x, 1.0, 1.0, 0.5, min_p=0.24)
+    assert abs(r["filter_margin"] - (0.25 - f32(0.24)) / f32(0.24)) < 1e-6
+    # min_p = 0.26 is as near to 1/4 from the other side
+    r = _full(oracle, x, 1.0, 1.0, 0.5, min_p=0.26)
+    assert abs(r["filter_margin"] - (f32(0.26) - 0.25) / f32(0.26)) < 1e-6
+    # min_p exactly on a probability (the maximum has p = 1 exactly): tokens on the threshold are not
+    # counted (distance 0) and stay; the nearest other probability is 1/2 -> margin 1/2
+    r = _full(oracle, np.float64([0.0, 0.0, np.log(0.5)]), 1.0, 1.0, 0.5, min_p=1.0)
+    assert abs(r["filter_margin"] - 0.5) < 1e-6 and r["kept"] == 2
+    # top_k = 2: tau_k = 1/2, the next smaller probability is 1/4 -> (1/2 - 1/4) / (1/2)
+    r = _full(oracle, x, 1.0, 1.0, 0.5, top_k=2)
+    assert abs(r["filter_margin"] - 0.5) < 1e-6
+    # top_k = 3: tau_k = 1/4, next 1/8 -> 1/2 again; top_k = 1: tau_k = 1, next 1/2 -> 1/2
+    assert abs(_full(oracle, x, 1.0, 1.0, 0.5, top_k=3)["filter_margin"] - 0.5) < 1e-6
+    # both filters: the smaller of the two margins
+    r = _full(oracle, x, 1.0, 1.0, 0.5, top_k=2, min_p=0.12)
+    assert abs(r["filter_margin"] - (0.125 - f32(0.12)) / f32(0.12)) < 1e-6
+    # unequal gaps tell the neighbours apart: p = 1, 0.9, 0.5 (index order 0.9, 1, 0.5), top_k = 2
+    y = np.log(np.float64([0.9, 1.0, 0.5]))
+    r = _full(oracle, y, 1.0, 1.0, 0.5, top_k=2)
+    assert abs(r["filter_margin"] - (0.9 - 0.5) / 0.9) < 1e-6
+    r = _full(oracle, y, 1.0, 1.0, 0.5, top_k=1)
+    assert abs(r["filter_margin"] - 0.1) < 1e-6
+
+
+def test_cut_margin_and_cdf_interval_of_the_filtered_rule(oracle):
+    x = np.log(np.float64([4.0, 8.0, 1.0, 2.0]))
+    # top_k = 3 leaves masses 1, 1/2, 1/4 (S2 = 7/4); top_p = 0.6 needs 1.05: running mass 1 then 3/2
+    # -> margin = min(|1 - 1.05|, |1.5 - 1.05|) / 1.75
+    r = _full(oracle, x, 1.0, 0.6, 0.99, top_k=3)
+    assert abs(r["cut_margin"] - abs(1.0 - f32(0.6) * 1.75) / 1.75) < 1e-6
+    # without top_k the same cut is measured against S = 15/8
+    r = _full(oracle, x, 1.0, 0.6, 0.99)
+    assert abs(r["cut_margin"] - abs(1.0 - f32(0.6) * 1.875) / 1.875) < 1e-6
+    # top_k = 2: kept masses in index order 1/2, 1 of 3/2 -> token 0 owns [0, 1/3), token 1 [1/3, 1)
+    r = _full(oracle, x, 1.0, 1.0, 0.30, top_k=2)
+    assert r["token"] == 0 and r["cdf_lo"] == 0.0 and abs(r["cdf_hi"] - 1.0 / 3.0) < 1e-6
+    r = _full(oracle, x, 1.0, 1.0, 0.34, top_k=2)
+    assert r["token"] == 1 and abs(r["cdf_lo"] - 1.0 / 3.0) < 1e-6 and abs(r["cdf_hi"] - 1.0) < 1e-6
+    # min_p = 0.2 drops the 1/8 token: intervals 2/7 | 6/7 | 1
+    r = _full(oracle, x, 1.0, 1.0, 0.5, min_p=0.2)
+    assert r["token"] == 1 and abs(r["cdf_lo"] - 2.0 / 7.0) < 1e-6 and abs(r["cdf_hi"] - 6.0 / 7.0) < 1e-6
