@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.sample_tokens_workspace_size.argtypes = [i64, i64]
     lib.sample_tokens.restype = ctypes.c_int
     lib.sample_tokens.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.sample_tokens_static.restype = ctypes.c_int
+    lib.sample_tokens_static.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp]
     lib.sample_tokens_filtered.restype = ctypes.c_int
     lib.sample_tokens_filtered.argtypes = [vp, ctypes.c_int32, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lp = ctypes.POINTER(PrefixLevel)
@@ -140,6 +142,15 @@ def sample_tokens(logits, logits_dtype: int, rows: int, vocab: int, row_stride: 
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "sample_tokens")
+
+
+def sample_tokens_static(logits, logits_dtype: int, rows: int, vocab: int, row_stride: int, temperature,
+                         top_p, uniforms, tokens_out, stream=None) -> None:
+    rc = load().sample_tokens_static(
+        _ptr(logits), logits_dtype, int(rows), int(vocab), int(row_stride), _ptr(temperature),
+        _ptr(top_p), _ptr(uniforms), _ptr(tokens_out), _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "sample_tokens_static")
 
 
 def append_suffix_kv(desc: AttnDesc, k_new, v_new, k_suffix, v_suffix, suffix_lens, suffix_page_indptr,

@@ -5,6 +5,13 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
+
+// Scratch memory of sample_tokens_static: one copy per GPU, held until the process ends.  In host
+// code this name only stands for the symbol; the memory is reached through the address that
+// hipGetSymbolAddress returns on each device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[SPD_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using spd::AttnParams;
@@ -112,6 +119,27 @@ int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix
 }
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return SPD_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return SPD_ELAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPD_OK;
+}
 
 }  // namespace
 
@@ -483,6 +511,22 @@ int sample_tokens(const void* logits, int32_t logits_dtype, int64_t rows, int64_
 {
     return sample_tokens_filtered(logits, logits_dtype, rows, vocab, row_stride, temperature, top_p, nullptr,
                                   nullptr, uniforms, tokens_out, workspace, workspace_bytes, stream);
+}
+
+int sample_tokens_static(const void* logits, int32_t logits_dtype, int64_t rows, int64_t vocab,
+                         int64_t row_stride, const float* temperature, const float* top_p,
+                         const float* uniforms, int32_t* tokens_out, void* stream)
+{
+    if (rows <= 0 || vocab <= 0)
+        return SPD_EINVAL;
+    if (sample_tokens_workspace_size(rows, vocab) > (size_t)SPD_STATIC_SCRATCH_BYTES)
+        return SPD_EWORKSPACE;  // more rows (or a larger vocabulary) than the library's own scratch holds
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != SPD_OK)
+        return rc;
+    return sample_tokens_filtered(logits, logits_dtype, rows, vocab, row_stride, temperature, top_p, nullptr,
+                                  nullptr, uniforms, tokens_out, ptr, (size_t)SPD_STATIC_SCRATCH_BYTES, stream);
 }
 
 int sample_tokens_filtered(const void* logits, int32_t logits_dtype, int64_t rows, int64_t vocab,
