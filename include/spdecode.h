@@ -34,6 +34,10 @@
  *     out of range, NaN logits, negative temperature) are the caller's
  *     responsibility: results are then undefined.
  *   - concurrent calls are safe if their workspaces and outputs are disjoint.
+ *   - range of V on the bf16 path: partial results travel between the kernels as fp16, so every
+ *     value row must satisfy |v| <= 65504 (anything a softmax-weighted average of such rows can
+ *     reach).  bf16 itself can hold larger magnitudes; results for them are undefined (inf or
+ *     NaN).  The fp32 path has no such limit.
  */
 #ifndef SPDECODE_H
 #define SPDECODE_H

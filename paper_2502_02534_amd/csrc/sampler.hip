@@ -1333,12 +1333,6 @@ int sampler_slices(long long rows, long long vocab)
     if (s > smax_small) s = smax_small;
     if (s > 8) s = 8;
     if (s < smin) s = smin;
-#ifdef SPD_TUNING
-    if (const char* e = getenv("SPD_TUNE_SAMPLER_SLICES")) {
-        const long long t = atoll(e);
-        if (t >= smin && t <= kMaxSlices) s = t;
-    }
-#endif
     return (int)s;
 }
 

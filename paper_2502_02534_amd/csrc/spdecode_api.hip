@@ -1,6 +1,7 @@
 // C ABI of libspdecode: argument validation, launch planning, kernel launches.
 #include "../../include/spdecode.h"
 #include "spd_internal.h"
+#include "plan.h"
 
 #include <math.h>
 #include <stdlib.h>
@@ -15,108 +16,7 @@ static __device__ __align__(256) unsigned char scratch[SPD_STATIC_SCRATCH_BYTES]
 namespace {
 
 using spd::AttnParams;
-
-struct Plan {
-    int prefix_split_tokens, num_prefix_splits;
-    int suffix_chunk_tokens, num_suffix_chunks;
-    size_t acc_bytes, ml_bytes;
-};
-
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-int check_desc(const spd_attn_desc* d)
-{
-    if (!d)
-        return SPD_EINVAL;
-    if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->head_dim <= 0 || d->num_prompts <= 0 ||
-        d->num_samples <= 0 || d->max_samples_per_prompt < 0)
-        return SPD_EINVAL;
-    if (d->num_q_heads % d->num_kv_heads != 0)
-        return SPD_EINVAL;
-    if (d->dtype != SPD_F32 && d->dtype != SPD_BF16)
-        return SPD_EUNSUPPORTED;
-    if (d->page_size != 0 && d->page_size != 16)
-        return SPD_EUNSUPPORTED;
-    if (d->head_dim > 256 || d->head_dim % 8 != 0)
-        return SPD_EUNSUPPORTED;
-    if (d->stages & ~(uint32_t)(SPD_STAGE_PREFIX | SPD_STAGE_SUFFIX | SPD_STAGE_MERGE))
-        return SPD_EINVAL;
-    return SPD_OK;
-}
-
-// Tokens per part so that at most `max_parts` parts cover `len`, in multiples of `quantum`.
-int part_tokens(long long len, int min_tokens, int max_parts, int quantum)
-{
-    long long t = (len + max_parts - 1) / max_parts;
-    if (t < min_tokens)
-        t = min_tokens;
-    t = (t + quantum - 1) / quantum * quantum;
-    return (int)t;
-}
-
-// Tokens per split of a prefix level with `groups` groups of at most `spp` samples and lengths up to
-// `max_prefix`, at most `max_splits` splits.
-int plan_prefix_split(const spd_attn_desc* d, int groups, int spp, long long max_prefix, int max_splits)
-{
-    int split;
-    if (d->dtype == SPD_BF16 && d->head_dim == 128) {
-        // tiled path: one workgroup per (group, KV head, row tile, split); enough splits to
-        // occupy every CU once, in multiples of the 64-token tile
-        const int rows = spp * (d->num_q_heads / d->num_kv_heads);
-        const int block_rows = spd::prefix_mfma_block_rows(rows);
-        const long long base = (long long)groups * d->num_kv_heads * ((rows + block_rows - 1) / block_rows);
-        long long want = (256 + base - 1) / base;
-        if (want > max_splits) want = max_splits;
-        long long t = (max_prefix + want - 1) / want;
-        t = (t + 63) / 64 * 64;
-        if (t < 128) t = 128;  // at least two tiles per split: a one-tile workgroup is all start-up
-        split = (int)t;
-    } else {
-        split = part_tokens(max_prefix, 256, max_splits, 64);
-    }
-#ifdef SPD_TUNING
-    if (const char* e = getenv("SPD_TUNE_PREFIX_SPLIT")) split = atoi(e);
-#endif
-    return split;
-}
-
-int make_plan(const spd_attn_desc* d, long long max_prefix, long long max_suffix, Plan* pl)
-{
-    const int rc = check_desc(d);
-    if (rc != SPD_OK)
-        return rc;
-    if (max_prefix < 0 || max_suffix < 0 || max_prefix > (1ll << 30) || max_suffix > (1ll << 30))
-        return SPD_EINVAL;
-    const int spp = d->max_samples_per_prompt > 0 ? d->max_samples_per_prompt : d->num_samples;
-    pl->prefix_split_tokens = plan_prefix_split(d, d->num_prompts, spp, max_prefix, 64);
-    pl->num_prefix_splits = (int)((max_prefix + pl->prefix_split_tokens - 1) / pl->prefix_split_tokens);
-    {
-        // enough (sample, KV head, chunk) items to keep every CU busy, chunks of 64..320 tokens
-        // (measured on ragged suffixes of up to 2048 tokens: 320-token chunks beat 512-token ones
-        // by 17 %, finer balance between wavefronts; the merge can take 64 chunks)
-        const long long pairs = (long long)d->num_samples * d->num_kv_heads;
-        const long long want_chunks = (2048 + pairs - 1) / pairs;
-        long long t = (max_suffix + want_chunks - 1) / want_chunks;
-        t = (t + 63) / 64 * 64;
-        if (t < 64) t = 64;
-        if (t > 320) t = 320;
-        // Chunks of 128 or 256 tokens start every wavefront of the launch at addresses that agree
-        // in many low bits (the rows of a sample are 2 KB apart), which costs 5 to 20 % of the
-        // HBM rate; three quarters of the size spreads them.
-        if (t == 128 || t == 256) t = t / 4 * 3;
-        if (max_suffix > t * 64) t = part_tokens(max_suffix, 64, 64, 64);
-#ifdef SPD_TUNING
-        if (const char* e = getenv("SPD_TUNE_SUFFIX_CHUNK")) t = atoi(e);
-#endif
-        pl->suffix_chunk_tokens = (int)t;
-    }
-    pl->num_suffix_chunks = (int)((max_suffix + pl->suffix_chunk_tokens - 1) / pl->suffix_chunk_tokens);
-    const size_t rows = (size_t)d->num_samples * d->num_q_heads;
-    const size_t slots = (size_t)pl->num_prefix_splits + pl->num_suffix_chunks;
-    pl->acc_bytes = align_up(slots * rows * d->head_dim * sizeof(float), 256);
-    pl->ml_bytes = align_up(slots * rows * sizeof(float2), 256);
-    return SPD_OK;
-}
+using namespace spd::plan;
 
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
 
@@ -224,46 +124,6 @@ size_t shared_prefix_decode_attn_workspace_size(const spd_attn_desc* desc, int64
 
 namespace {
 
-// Plan of a multi-level call: split size and count per level, slot offsets, suffix chunks.
-struct LevelPlan {
-    int split_tokens[SPD_MAX_PREFIX_LEVELS], num_splits[SPD_MAX_PREFIX_LEVELS], slot0[SPD_MAX_PREFIX_LEVELS];
-    int suffix_chunk_tokens, num_suffix_chunks, num_slots;
-    size_t acc_bytes, ml_bytes;
-};
-
-int make_level_plan(const spd_attn_desc* d, int num_levels, const spd_prefix_level* levels, long long max_suffix,
-                    LevelPlan* lp)
-{
-    if (num_levels < 1 || num_levels > SPD_MAX_PREFIX_LEVELS || !levels)
-        return SPD_EINVAL;
-    Plan pl;
-    spd_attn_desc tmp = *d;
-    tmp.num_prompts = 1;
-    tmp.max_samples_per_prompt = 0;
-    const int rc = make_plan(&tmp, 0, max_suffix, &pl);  // validates desc and plans the suffix chunks
-    if (rc != SPD_OK)
-        return rc;
-    lp->suffix_chunk_tokens = pl.suffix_chunk_tokens;
-    lp->num_suffix_chunks = pl.num_suffix_chunks;
-    const int max_splits = 64 / num_levels;  // the merge takes 64 prefix splits in all
-    int slots = 0;
-    for (int l = 0; l < num_levels; ++l) {
-        const spd_prefix_level& L = levels[l];
-        if (L.num_groups < 1 || L.max_samples_per_group < 0 || L.max_len < 0 || L.max_len > (1ll << 30))
-            return SPD_EINVAL;
-        const int spp = L.max_samples_per_group > 0 ? L.max_samples_per_group : d->num_samples;
-        lp->split_tokens[l] = plan_prefix_split(d, L.num_groups, spp, L.max_len, max_splits);
-        lp->num_splits[l] = (int)((L.max_len + lp->split_tokens[l] - 1) / lp->split_tokens[l]);
-        lp->slot0[l] = slots;
-        slots += lp->num_splits[l];
-    }
-    lp->num_slots = slots + lp->num_suffix_chunks;
-    const size_t rows = (size_t)d->num_samples * d->num_q_heads;
-    lp->acc_bytes = align_up((size_t)lp->num_slots * rows * d->head_dim * sizeof(float), 256);
-    lp->ml_bytes = align_up((size_t)lp->num_slots * rows * sizeof(float2), 256);
-    return SPD_OK;
-}
-
 // The attention call proper: any number of prefix levels.  `stages` as in spd_attn_desc.
 int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, const spd_prefix_level* levels,
                   const LevelPlan& lp, const void* k_suffix, const void* v_suffix, const int32_t* suffix_lens,
@@ -358,10 +218,7 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
         }
         for (int l = fl.num_levels + 1; l <= spd::kMaxLevels; ++l)
             fl.first_block[l] = (int)blocks;
-        bool one_launch = fl.num_levels >= 1 && blocks < 0x7fffffffLL && spd::attn_fused_levels_supported(p, fl);
-#ifdef SPD_TUNING
-        if (getenv("SPD_TUNE_NO_FUSED")) one_launch = false;
-#endif
+        const bool one_launch = fl.num_levels >= 1 && blocks < 0x7fffffffLL && spd::attn_fused_levels_supported(p, fl);
         if (one_launch) {
             if (spd::launch_attn_fused_levels(p, fl, s) != hipSuccess)
                 return SPD_ELAUNCH;
@@ -400,10 +257,7 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
         e = spd::launch_attn_plain(p, want_prefix && !prefix_tiled, want_suffix && !suffix_tiled, s);
         if (e != hipSuccess)
             return SPD_ELAUNCH;
-        bool fused = want_prefix && want_suffix && spd::attn_fused_supported(p);
-#ifdef SPD_TUNING
-        if (getenv("SPD_TUNE_NO_FUSED")) fused = false;
-#endif
+        const bool fused = want_prefix && want_suffix && spd::attn_fused_supported(p);
         if (fused) {
             e = spd::launch_attn_fused(p, s);
             if (e != hipSuccess)

@@ -222,3 +222,17 @@ def test_wide_prefix_workgroups_on_their_own_launch(dev, oracle, page):
     check_attention(dev, oracle, inp, rows=rows)
     inp.q = _bits(W.bf16_bits_to_f32(inp.q) * np.float32(4.0))
     check_attention(dev, oracle, inp, rows=rows)
+
+
+def test_large_values_within_the_stated_range(dev, oracle):
+    """V scaled by 2^13 (largest magnitude about 4e4, inside the documented |v| <= 65504 of the bf16
+    path, whose partial results are fp16): the output is the unscaled one times 2^13."""
+    print("V scaled by 8192", flush=True)
+    inp = W.make_attn_inputs(0, spec=W.small_spec(**SHAPES["fused"]), seed=16)
+    ref, _ = oracle.attention_inputs(inp)
+    big = copy.copy(inp)
+    big.v_prefix = _bits(W.bf16_bits_to_f32(inp.v_prefix) * np.float32(8192.0))
+    big.v_suffix = _bits(W.bf16_bits_to_f32(inp.v_suffix) * np.float32(8192.0))
+    assert np.abs(_f(big.v_prefix)).max() > 3e4
+    out, _ = _run(dev, big)
+    attention_errors(out / 8192.0, ref, "bf16")
