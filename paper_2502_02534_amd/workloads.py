@@ -17,7 +17,9 @@ patterns produced by round-to-nearest-even from float32 normals.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
+import os
 from typing import Optional
 
 import numpy as np
@@ -81,16 +83,28 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def _normal(rng: np.random.Generator, shape, dtype: str, sigma: float = 1.0) -> np.ndarray:
-    """N(0, sigma^2) of the given shape; drawn in slabs to bound peak memory."""
+    """N(0, sigma^2) of the given shape.  The array is cut into slabs of 2^24 values; slab i is drawn
+    from the i-th child stream of `rng`, so the result does not depend on how many threads draw."""
     n = int(np.prod(shape)) if len(shape) else 1
     out = np.empty(n, dtype=np.uint16 if dtype == "bf16" else np.float32)
     slab = 1 << 24
-    for s in range(0, n, slab):
+    starts = list(range(0, n, slab))
+    streams = rng.spawn(len(starts)) if starts else []
+
+    def fill(i):
+        s = starts[i]
         e = min(n, s + slab)
-        v = rng.standard_normal(e - s, dtype=np.float32)
+        v = streams[i].standard_normal(e - s, dtype=np.float32)
         if sigma != 1.0:
             v *= np.float32(sigma)
         out[s:e] = f32_to_bf16_bits(v) if dtype == "bf16" else v
+
+    if len(starts) > 1:
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            list(pool.map(fill, range(len(starts))))
+    else:
+        for i in range(len(starts)):
+            fill(i)
     return out.reshape(shape)
 
 
