@@ -223,13 +223,13 @@ SPD_API int sample_tokens(const void *logits, int32_t logits_dtype,
  * and the call allocates and frees nothing.
  *
  * Limit: sample_tokens_workspace_size(rows, vocab) must not exceed SPD_STATIC_SCRATCH_BYTES
- * (about 75 rows of a 128k vocabulary); larger problems return SPD_EWORKSPACE and launch nothing.
+ * (about 95 rows of a 128k vocabulary); larger problems return SPD_EWORKSPACE and launch nothing.
  * All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different
  * streams, or the same graph launched twice at once) race on it and give undefined tokens; calls
  * that follow one another on a stream are fine, whatever their sizes (every call resets what it
  * needs to find at zero).
  */
-#define SPD_STATIC_SCRATCH_BYTES (8u << 20)
+#define SPD_STATIC_SCRATCH_BYTES (16u << 20)
 SPD_API int sample_tokens_static(const void *logits, int32_t logits_dtype,
                          int64_t rows, int64_t vocab, int64_t row_stride,
                          const float *temperature, const float *top_p, const float *uniforms,

@@ -14,6 +14,7 @@
 #include "spd_internal.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace spd {
 namespace {
@@ -403,101 +404,83 @@ __device__ void sample_row_from_memory(const SamplerParams& sp, long long r, Row
 
 // =============================================================================================
 // Sliced path: a row is cut into `slices` contiguous pieces of at most kSliceMax elements and
-// handled by two kernels in stream order (no workgroup ever waits for another):
+// handled by two kernels in stream order; no workgroup ever waits for another and there are no
+// cross-workgroup counters.
 //
-//   hist    (rows x slices)  one HBM pass: slice maximum (and its lowest index) and a histogram
-//           of scaled mass over bins of width 1/16 in log2 p.  The bin of a logit is
-//           floor(x c 16), an integer function of x alone; a histogram built against the slice
-//           maximum differs from one built against the row maximum by an integer shift.
-//           Mass is accumulated in u32 fixed point relative to the bin's own reference
-//           (q = 2^(frac/16) 2^15 in [32768, 34219]), which needs no maximum at all.
-//   select  (rows x slices)  second look at the slice (served by cache when the logits fit).
-//           Every workgroup first combines the row's slice histograms and picks the bin that
-//           holds the nucleus cut, plus a neighbour when the estimate cannot decide (the same
-//           arithmetic in every workgroup of a row, so they agree).  Then, with
-//           p_i = 2^((x_i - row max) c) exactly as defined: slice mass in fp64, mass of the
-//           certainly-kept elements per 256-element segment in vocabulary order, and the
-//           elements of the cut bins as candidates (logit, index).  The workgroup of a row that
-//           finishes last finds the exact threshold among the candidates by radix select on the
-//           logit's bit pattern with fp64 masses, adds the kept candidates to their segments,
-//           scans the segments and walks inside the segment that contains u * Z.
+//   scan    (rows x slices)  the one pass over the logits.  A workgroup holds its slice in
+//           registers and leaves behind everything the row-level step can need from it:
+//           the slice maximum (and its lowest index), the slice mass relative to that maximum,
+//           a histogram of mass over bins of width 1/16 in log2 p (the bin of a logit is
+//           floor(x c 16), an integer function of x alone, so a slice histogram differs from
+//           the row's by an integer shift; mass is accumulated in u32 fixed point relative to the
+//           bin's own reference), and the elements the nucleus cut can fall among, written out as
+//           (logit, index) pairs.  Which elements those are is a local guess: the slice finds its
+//           own cut bin L from its own histogram; if the slice's elements down to a few bins
+//           past L fit the budget it emits from the top (bins 0 .. L + margin, as far as the
+//           budget goes), otherwise a window of bins centred on L, as wide as the budget allows,
+//           and it sums the mass above the window per 256-element segment.  A slice whose cut bin
+//           alone exceeds the budget emits nothing.
+//   finish  (rows)  combines the slice maxima and histograms into the row's cut bins [lo, hi].
+//           A slice is "covered" if its emitted bins contain [lo, hi] and everything it summed as
+//           above its window really is above lo; its emitted elements are then classified with
+//           p_i = 2^((x_i - row max) c) exactly as defined (kept for certain, candidate, dropped).
+//           Slices that are not covered are read a second time by this workgroup.  The exact
+//           threshold is found among the candidates by radix select on the logit's bit pattern
+//           with fp64 masses; kept candidates join their segments; the segments are scanned and
+//           the walk ends inside the segment that contains u * Z.
 //
-// What the workgroups of a row hand to the last one goes through memory with agent-scope
-// accesses (written through, read past the local L2), ordered by an arrival counter.
+// With the row statistics exchanged through memory between two kernels, plain stores and loads do.
 // =============================================================================================
 constexpr int kIter = kBlock * 4;         // elements one float4 per thread covers
 constexpr int kSliceMax = 8 * kIter;      // elements per workgroup: 8 float4 per thread
 constexpr int kMaxSlices = 16;
 constexpr int kSegPerSlice = kSliceMax / kSeg;  // 64
 constexpr int kCandCap = 4096;
-constexpr int kPubBins = 1024;   // histogram bins a slice publishes (64 octaves below its maximum)
+constexpr int kPubBins = 1024;    // histogram bins of a slice (64 octaves below its maximum)
+constexpr int kEmitCap = 2048;    // (logit, index) pairs a slice may write out
+constexpr int kTopProbe = 0;      // a slice emits from the top if its elements down to L + kTopProbe fit
+constexpr int kTopMargin = 160;   // ... and then goes on down to L + kTopMargin at most (10 octaves)
 static_assert(kMaxSlices * kSegPerSlice <= kMaxSegments, "segment table too small");
 
 struct SliceStat {
     float max_x;
     int argmax;
-    double mass;    // sum of p over the slice (select kernel)
-    double above;   // mass of certainly-kept elements (select kernel)
+    double rest;      // estimated mass of the slice's bins past win_hi, in units of 2^(bin_coord(max_x) / 16)
+    double pair_mass; // sum of 2^((x - max_x) c) over the pairs written out
+    int win_lo;       // emitted bins [win_lo, win_hi], counted down from the bin of max_x
+    int win_hi;
+    int count;        // emitted pairs; -1: the slice emitted nothing although the row has a cut
+    int pad;
 };
-
-// Counters of a row, zeroed by the hist kernel for the select kernel that follows it.
-struct RowCtl {
-    unsigned arrived;     // workgroups of the row that have published their results
-    unsigned cand_total;  // candidates appended so far
-    int lo, hi;           // cut bins, when the per-row cut kernel ran
-};
+static_assert(sizeof(SliceStat) <= 64, "slice statistics are kept 64 bytes apart");
 
 __host__ __device__ inline size_t sliced_row_bytes(int slices)
 {
-    return 256 + (size_t)slices * 64 + (size_t)slices * kPubBins * 4 + (size_t)slices * kSegPerSlice * 8 +
-           (size_t)kCandCap * 8;
+    return (size_t)slices * (64 + (size_t)kPubBins * 4 + (size_t)kSegPerSlice * 8 + (size_t)kEmitCap * 8);
 }
 
 struct RowWs {
-    RowCtl* ctl;
-    SliceStat* stat;      // [slices], 64 B apart
-    unsigned* hist;       // [slices][kPubBins]
-    double* seg;          // [slices][kSegPerSlice]
-    unsigned long long* cand;  // [kCandCap] logit bits | index << 32
+    char* stat;                // [slices] SliceStat, 64 B apart
+    unsigned* hist;            // [slices][kPubBins]
+    double* seg;               // [slices][kSegPerSlice] mass above the window (whole mass when nothing is cut)
+    unsigned long long* emit;  // [slices][kEmitCap] logit bits | index << 32
 };
 
 __device__ __forceinline__ RowWs row_ws(char* base, long long row, int slices)
 {
     char* p = base + row * sliced_row_bytes(slices);
     RowWs w;
-    w.ctl = (RowCtl*)p;
-    p += 256;
-    w.stat = (SliceStat*)p;
+    w.stat = p;
     p += (size_t)slices * 64;
     w.hist = (unsigned*)p;
     p += (size_t)slices * kPubBins * 4;
     w.seg = (double*)p;
     p += (size_t)slices * kSegPerSlice * 8;
-    w.cand = (unsigned long long*)p;
+    w.emit = (unsigned long long*)p;
     return w;
 }
 
-__device__ __forceinline__ SliceStat* stat_at(const RowWs& w, int s)
-{
-    return (SliceStat*)((char*)w.stat + (size_t)s * 64);
-}
-
-// Agent-scope accesses for data that one workgroup writes and another reads inside one kernel:
-// written through and read past the local L2, ordered by the row's arrival counter (the writer
-// waits for its stores to be acknowledged before it counts).  A release / acquire pair on the
-// counter instead was measured 13 us slower per call: an agent-scope release writes the L2 back.
-// When the reader is a later kernel (`across_kernels`), ordinary stores do.
-template <typename T> __device__ __forceinline__ void publish(T* p, T v, bool across_kernels)
-{
-    if (across_kernels)
-        *p = v;
-    else
-        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T> __device__ __forceinline__ T observe(const T* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+__device__ __forceinline__ SliceStat* stat_at(const RowWs& w, int s) { return (SliceStat*)(w.stat + (size_t)s * 64); }
 
 // Monotone map of a float onto unsigned integers (larger float -> larger key).
 __device__ __forceinline__ uint32_t order_key(float x)
@@ -528,6 +511,14 @@ __device__ __forceinline__ RowConst row_const(float T)
     k.c_lo = (float)(k.cd - (double)k.c_hi);
     k.c16 = k.c_hi * 16.f;
     return k;
+}
+
+// Mass that one unit of a bin's fixed-point histogram stands for, relative to the reference of
+// bin 0: 2^-15 2^(-bin/16) (the root in fp32: an estimate is all that is needed).
+__device__ __forceinline__ double bin_unit(int bin)
+{
+    const double root = (double)__builtin_amdgcn_exp2f(-0.0625f * (float)(bin & 15));
+    return root * __hiloint2double((1023 - 15 - (bin >> 4)) << 20, 0);
 }
 
 // Loads the slice [e0, e1) of a row into 32 registers per thread (whole float4s only; lanes
@@ -570,13 +561,94 @@ __device__ __forceinline__ SliceRange slice_range(int slice, int slice_elems, in
         }                                                                               \
     }
 
-// ---- kernel 1: slice maximum and histogram -----------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, char* ws, int slices,
-                                                              int slice_elems)
+// Largest b in [lo_b, hi_b] with pred(b), where pred is true on a prefix of the range; lo_b - 1
+// if it is false everywhere.
+template <typename F> __device__ __forceinline__ int last_true(int lo_b, int hi_b, F pred)
 {
-    __shared__ unsigned hist[kPubBins];
-    __shared__ float red_f[kWaves];
-    __shared__ int red_i[kWaves];
+    int lo = lo_b - 1, hi = hi_b;  // invariant: pred(lo) (or lo == lo_b - 1), answer <= hi
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pred(mid))
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// ---- kernel 1: the pass over the logits --------------------------------------------------------------
+struct ScanLds {
+    unsigned hist[kPubBins];
+    unsigned cumq[kPubBins];            // inclusive running sum of hist
+    unsigned long long stage[kEmitCap]; // the slice's list, gathered here and copied out in one piece
+    double wave_mass[kWaves];
+    unsigned wave_q[kWaves];
+    float red_f[kWaves];
+    int red_i[kWaves];
+    double rest;               // estimated mass of the bins past the window
+    double pair_mass[kWaves];  // exact mass of the pairs each wavefront gathered
+    int cut_bin;               // the slice's own cut bin L
+    int best;                  // scratch of the window search
+    int emitted;               // places reserved in the slice's list so far
+};
+
+// Barrier between phases that exchange data through LDS only: waits for this wavefront's LDS
+// traffic, not for its global loads and stores (a __syncthreads would drain those too, and the
+// slice's logits and the published results are still in flight at most barriers of this kernel).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Fixed-point mass of a logit inside its bin: 32768 2^(f/16) for f in [0, 1), as a cubic in f
+// (the next term of the series is below 0.005 units).
+__device__ __forceinline__ unsigned bin_units(float f)
+{
+    const float a1 = 1419.5653f, a2 = 30.749034f, a3 = 0.44403f;
+    return (unsigned)__builtin_fmaf(__builtin_fmaf(__builtin_fmaf(a3, f, a2), f, a1), f, 32768.5f);
+}
+
+__device__ __forceinline__ int wave_max_i32(int v)
+{
+    for (int o = 32; o > 0; o >>= 1)
+        v = max(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Folds eight per-lane partial sums (one per 256-element segment j of the wavefront's pass) across the
+// wavefront: after the exchange across 32 lanes each half keeps four segments, then two, then one,
+// so that lane 8 s ends up with the sum of segment s (10 exchanges instead of 48).
+__device__ __forceinline__ float fold_segments(const float (&s_seg)[8])
+{
+    const int lane = threadIdx.x & 63;
+    const bool up32 = (lane & 32) != 0, up16 = (lane & 16) != 0, up8 = (lane & 8) != 0;
+    float a4[4], a2[2], a1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float keep = up32 ? s_seg[4 + j] : s_seg[j];
+        const float give = up32 ? s_seg[j] : s_seg[4 + j];
+        a4[j] = keep + __shfl_xor(give, 32);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const float keep = up16 ? a4[2 + j] : a4[j];
+        const float give = up16 ? a4[j] : a4[2 + j];
+        a2[j] = keep + __shfl_xor(give, 16);
+    }
+    {
+        const float keep = up8 ? a2[1] : a2[0];
+        const float give = up8 ? a2[0] : a2[1];
+        a1 = keep + __shfl_xor(give, 8);
+    }
+    a1 += __shfl_xor(a1, 4);
+    a1 += __shfl_xor(a1, 2);
+    a1 += __shfl_xor(a1, 1);
+    return a1;  // lanes 8 s .. 8 s + 7 hold segment j = 4 (lane/32) + 2 (lane/16 % 2) + lane/8 % 2 = lane >> 3
+}
+
+__global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
+{
+    __shared__ ScanLds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long r = blockIdx.x / slices;
     const int slice = blockIdx.x % slices;
@@ -585,79 +657,317 @@ __global__ __launch_bounds__(kBlock) void sampler_hist_kernel(SamplerParams sp, 
     const RowWs W = row_ws(ws, r, slices);
     const float T = sp.temperature[r];
     const bool greedy = (T == 0.f);
-    const bool cut = !greedy && sp.top_p[r] < 1.f;
+    const float top_p = sp.top_p[r];
+    const bool cut = !greedy && top_p < 1.f;
 
     float xv[32];
     SPD_LOAD_SLICE(xv, x, g, tid)
-    SPD_MASK_SLICE(xv, g, tid)
-    if (slice == 0 && tid == 0) {
-        W.ctl->arrived = 0u;
-        W.ctl->cand_total = 0u;
+    float tail[3] = {-INFINITY, -INFINITY, -INFINITY};  // the row's last one to three logits (thread 0 of the last slice)
+    if (tid == 0)
+        for (int k = 0; k < 3; ++k)
+            if (k < g.ntail)
+                tail[k] = x[g.v4end + k];
+    for (int b = tid; b < kPubBins; b += kBlock)
+        L.hist[b] = 0u;
+    if (tid == 0) {
+        L.cut_bin = kPubBins - 1;
+        L.best = -1;
+        L.emitted = 0;
+        L.rest = 0.0;
     }
-    float mx = -INFINITY;
+    // wavefronts whose 32 x 64 x 4 logits all lie inside the slice skip the end-of-slice tests
+    const bool whole = g.e0 + 7 * kIter + (tid | 63) * 4 + 4 <= g.v4end;
+    if (!whole) {
+        SPD_MASK_SLICE(xv, g, tid)
+    }
+    float mx = fmaxf(fmaxf(tail[0], tail[1]), tail[2]);
 #pragma unroll
     for (int q = 0; q < 32; ++q)
         mx = fmaxf(mx, xv[q]);
-    if (tid == 0)
-        for (int k = 0; k < g.ntail; ++k)
-            mx = fmaxf(mx, x[g.v4end + k]);
     for (int o = 32; o > 0; o >>= 1)
         mx = fmaxf(mx, __shfl_xor(mx, o));
     if (lane == 0)
-        red_f[wave] = mx;
-    for (int b = tid; b < kPubBins; b += kBlock)
-        hist[b] = 0u;
-    __syncthreads();
-    mx = red_f[0];
+        L.red_f[wave] = mx;
+    lds_barrier();
+    mx = L.red_f[0];
     for (int w = 1; w < kWaves; ++w)
-        mx = fmaxf(mx, red_f[w]);
+        mx = fmaxf(mx, L.red_f[w]);
 
-    int mi = 0x7fffffff;
     if (greedy) {
+        int mi = 0x7fffffff;
 #pragma unroll
         for (int q = 31; q >= 0; --q)
             if (xv[q] == mx)
                 mi = g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3);
-        if (tid == 0)
-            for (int k = g.ntail - 1; k >= 0; --k)
-                if (x[g.v4end + k] == mx)
-                    mi = min(mi, g.v4end + k);
+        for (int k = 2; k >= 0; --k)
+            if (tail[k] == mx)  // (-inf where there is no tail logit, and a slice maximum is finite)
+                mi = min(mi, g.v4end + k);
         for (int o = 32; o > 0; o >>= 1)
             mi = min(mi, __shfl_xor(mi, o));
         if (lane == 0)
-            red_i[wave] = mi;
-        __syncthreads();
-        for (int w = 0; w < kWaves; ++w)
-            mi = min(mi, red_i[w]);
+            L.red_i[wave] = mi;
+        lds_barrier();
+        if (tid == 0) {
+            for (int w = 0; w < kWaves; ++w)
+                mi = min(mi, L.red_i[w]);
+            SliceStat* st = stat_at(W, slice);
+            st->max_x = mx;
+            st->argmax = mi;
+        }
+        return;
     }
 
-    if (cut) {
-        const RowConst rc = row_const(T);
-        const float kf_loc = bin_coord(mx, rc.c16);
-        auto add = [&](float xq) {
-            const float t = xq * rc.c16;
-            const float kf = floorf(t);
-            const int b = min(bin_below(kf_loc, kf), kPubBins - 1);
-            // mass relative to the bin's own reference 2^(kf/16): 2^(frac/16) in [1, 2^(1/16))
-            const unsigned q = (unsigned)(__builtin_amdgcn_exp2f((t - kf) * 0.0625f) * 32768.f + 0.5f);
-            atomicAdd(&hist[b], q);
-        };
+    const RowConst rc = row_const(T);
+    RowScale rs;
+    rs.max_x = mx;
+    rs.c_hi = rc.c_hi;
+    rs.c_lo = rc.c_lo;
+    const float kf_loc = bin_coord(mx, rc.c16);
+    unsigned long long* out = W.emit + (size_t)slice * kEmitCap;
+    double* seg_out = W.seg + (size_t)slice * kSegPerSlice;
+
+    if (!cut) {
+        // ---- nothing is cut: the mass of every 256-element segment, relative to the slice maximum; the
+        // row's tail logits travel as pairs ----
+        float s_seg[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            s_seg[j] = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float xq = xv[4 * j + k];
+                s_seg[j] += (whole || xq != -INFINITY) ? prob(xq, rs) : 0.f;
+            }
+        }
+        const float a1 = fold_segments(s_seg);
+        if ((lane & 7) == 0)
+            seg_out[(lane >> 3) * kWaves + wave] = (double)a1;
+        if (tid == 0) {
+            int n = 0;
+            for (int k = 0; k < 3; ++k)
+                if (tail[k] != -INFINITY)
+                    out[n++] = (unsigned long long)__float_as_uint(tail[k]) | ((unsigned long long)(unsigned)(g.v4end + k) << 32);
+            SliceStat* st = stat_at(W, slice);
+            st->max_x = mx;
+            st->argmax = 0;
+            st->rest = 0.0;
+            st->pair_mass = 0.0;
+            st->win_lo = 0;
+            st->win_hi = -1;
+            st->count = n;
+        }
+        return;
+    }
+
+    // ---- histogram of mass over the slice's own bins.  Elements 64 octaves and more below the slice
+    // maximum share the last bin; they are counted per thread and added once (they would otherwise
+    // all meet at one LDS address). ----
+    unsigned far_units = 0u;
+    auto bin_one = [&](float xq) __attribute__((always_inline)) {
+        const float t = xq * rc.c16;
+        const float kf = floorf(t);
+        const float bf = kf_loc - kf;  // >= 0: kf_loc belongs to the maximum
+        const unsigned u = bin_units(t - kf);
+        if (bf < (float)(kPubBins - 1))
+            atomicAdd(&L.hist[(int)bf], u);
+        else
+            far_units += u;
+    };
+    if (whole) {
+#pragma unroll
+        for (int q = 0; q < 32; ++q)
+            bin_one(xv[q]);
+    } else {
 #pragma unroll
         for (int q = 0; q < 32; ++q)
             if (xv[q] != -INFINITY)
-                add(xv[q]);
-        if (tid == 0)
-            for (int k = 0; k < g.ntail; ++k)
-                add(x[g.v4end + k]);
-        __syncthreads();  // histogram complete
-        for (int b = tid; b < kPubBins; b += kBlock)
-            W.hist[(size_t)slice * kPubBins + b] = hist[b];
+                bin_one(xv[q]);
     }
+    for (int k = 0; k < 3; ++k)
+        if (tail[k] != -INFINITY)
+            bin_one(tail[k]);
+    for (int o = 32; o > 0; o >>= 1)
+        far_units += __shfl_xor(far_units, o);
+    if (lane == 0 && far_units)
+        atomicAdd(&L.hist[kPubBins - 1], far_units);
+    lds_barrier();  // histogram complete
+
+    // ---- running sums over the bins (thread t owns bins 2t, 2t+1): fixed-point units for the element
+    // counts, estimated mass for the slice's own cut bin ----
+    const unsigned q0 = L.hist[2 * tid], q1 = L.hist[2 * tid + 1];
+    const double m0 = (double)q0 * bin_unit(2 * tid), m1 = (double)q1 * bin_unit(2 * tid + 1);
+    unsigned qi = q0 + q1;
+    double mi = m0 + m1;
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned uq = __shfl_up(qi, o);
+        const double um = __shfl_up(mi, o);
+        if (lane >= o) {
+            qi += uq;
+            mi += um;
+        }
+    }
+    if (lane == 63) {
+        L.wave_q[wave] = qi;
+        L.wave_mass[wave] = mi;
+    }
+    lds_barrier();
+    unsigned qbefore = 0u;
+    double mbefore = 0.0, mtotal = 0.0;
+    for (int w = 0; w < kWaves; ++w) {
+        if (w < wave) {
+            qbefore += L.wave_q[w];
+            mbefore += L.wave_mass[w];
+        }
+        mtotal += L.wave_mass[w];
+    }
+    qi += qbefore;   // inclusive through bin 2t+1
+    mi += mbefore;
+    L.cumq[2 * tid] = qi - q1;
+    L.cumq[2 * tid + 1] = qi;
+    // the one thread whose bins take the running mass across top_p of the total names the cut bin
+    const double need = (double)top_p * mtotal;
+    if (mi - m0 - m1 < need) {
+        if (mi - m1 >= need)
+            L.cut_bin = 2 * tid;
+        else if (mi >= need)
+            L.cut_bin = 2 * tid + 1;
+    }
+    lds_barrier();
+    // ---- which bins to write out.  Element counts come from the fixed-point sums: every element adds
+    // between 32768 and 34219 units, so (units >> 15) never undercounts.  Every thread tests two
+    // places of the search range; the largest that fits wins. ----
+    const int cap = kEmitCap - 3;  // room for the row's tail logits
+    const int Lb = L.cut_bin;
+    auto units = [&](int a, int z) { return L.cumq[z] - (a > 0 ? L.cumq[a - 1] : 0u); };
+    auto fits = [&](int a, int z) { return (int)(units(a, z) >> 15) <= cap; };
+    const bool from_top = fits(0, min(Lb + kTopProbe, kPubBins - 1));
+    int mine = -1;
+    if (from_top) {
+        // bins 0 .. z, z as large as fits, at most L + kTopMargin
+        const int zmax = min(Lb + kTopMargin, kPubBins - 1);
+        if (2 * tid + 1 <= zmax && (int)(qi >> 15) <= cap)
+            mine = 2 * tid + 1;
+        else if (2 * tid <= zmax && (int)((qi - q1) >> 15) <= cap)
+            mine = 2 * tid;
+    } else if (fits(Lb, Lb)) {
+        // bins L - w .. L + w, w as large as fits
+#pragma unroll
+        for (int k = 1; k >= 0; --k) {
+            const int w = tid + k * kBlock;
+            if (mine < 0 && fits(max(Lb - w, 0), min(Lb + w, kPubBins - 1)))
+                mine = w;
+        }
+    }
+    mine = wave_max_i32(mine);
+    if (lane == 0 && mine >= 0)
+        atomicMax(&L.best, mine);
+    lds_barrier();
+    const int best = L.best;
+    int win_lo = 0, win_hi = -1;   // bins written out; win_hi < 0: none
+    if (best >= 0) {
+        win_lo = from_top ? 0 : max(Lb - best, 0);
+        win_hi = from_top ? best : min(Lb + best, kPubBins - 1);
+    }
+    // the thread that owns bin win_hi knows the estimated mass of everything past it
+    if (win_hi >= 0 && (win_hi >> 1) == tid)
+        L.rest = mtotal - ((win_hi & 1) ? mi : mi - m1);
+    // Bin tests without forming the bin: with t = x c16, bin(x) < a  <=>  floor(t) > kf_loc - a
+    // <=>  t >= kf_loc - a + 1 (both sides of the middle inequality are integers); likewise
+    // bin(x) <= z  <=>  t >= kf_loc - z, and the last bin takes everything below it (every finite
+    // logit: positions past the end of the slice hold -inf and fail the test).
+    const float t_above = win_lo <= 0 ? INFINITY : kf_loc - (float)win_lo + 1.f;
+    const float t_emit = win_hi < 0 ? INFINITY : (win_hi >= kPubBins - 1 ? -3.0e38f : kf_loc - (float)win_hi);
+
+    // ---- places in the slice's list: count per thread, running count over the wavefront, one
+    // reservation per wavefront; the pairs are gathered in LDS and copied out in one piece ----
+    int nemit = 0;
+    if (win_hi >= 0) {
+        if (win_lo <= 0) {
+#pragma unroll
+            for (int q = 0; q < 32; ++q)
+                nemit += xv[q] * rc.c16 >= t_emit ? 1 : 0;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 32; ++q) {
+                const float t = xv[q] * rc.c16;
+                nemit += (t >= t_emit && t < t_above) ? 1 : 0;
+            }
+        }
+    }
+    bool tail_out[3];
+    for (int k = 0; k < 3; ++k) {
+        tail_out[k] = win_hi >= 0 && tail[k] * rc.c16 >= t_emit;  // (-inf where there is no tail logit)
+        nemit += tail_out[k] ? 1 : 0;
+    }
+    int incl = nemit;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o)
+            incl += up;
+    }
+    int base = 0;
+    if (lane == 63 && incl)
+        base = atomicAdd(&L.emitted, incl);
+    base = __shfl(base, 63);
+    float pm = 0.f;  // exact mass of this thread's pairs
+    if (nemit) {
+        int pos = base + incl - nemit;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            const float t = xv[q] * rc.c16;
+            if (t >= t_emit && t < t_above) {
+                pm += prob(xv[q], rs);
+                if (pos < kEmitCap)
+                    L.stage[pos] = (unsigned long long)__float_as_uint(xv[q]) |
+                                   ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32);
+                ++pos;
+            }
+        }
+        for (int k = 0; k < 3; ++k)
+            if (tail_out[k]) {
+                pm += prob(tail[k], rs);
+                if (pos < kEmitCap)
+                    L.stage[pos] = (unsigned long long)__float_as_uint(tail[k]) | ((unsigned long long)(unsigned)(g.v4end + k) << 32);
+                ++pos;
+            }
+    }
+    {
+        const double wm = wave_sum_f64((double)pm);
+        if (lane == 0)
+            L.pair_mass[wave] = wm;
+    }
+    lds_barrier();
+    const int total = min(L.emitted, kEmitCap);
     if (tid == 0) {
         SliceStat* st = stat_at(W, slice);
         st->max_x = mx;
-        st->argmax = mi;
+        st->argmax = 0;
+        st->rest = L.rest;
+        double pmass = 0.0;
+        for (int w = 0; w < kWaves; ++w)
+            pmass += L.pair_mass[w];
+        st->pair_mass = pmass;
+        st->win_lo = win_lo;
+        st->win_hi = win_hi;
+        st->count = win_hi < 0 ? -1 : total;
     }
+    for (int i = tid; i < total; i += kBlock)
+        out[i] = L.stage[i];
+    *reinterpret_cast<uint2*>(&W.hist[(size_t)slice * kPubBins + 2 * tid]) = make_uint2(q0, q1);
+    // ---- segment sums: what lies above the window (nothing when the window starts at the top) ----
+    float s_seg[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        s_seg[j] = 0.f;
+    if (win_hi >= 0 && win_lo > 0) {
+#pragma unroll
+        for (int q = 0; q < 32; ++q)
+            if (xv[q] * rc.c16 >= t_above)
+                s_seg[q >> 2] += prob(xv[q], rs);
+    }
+    const float a1 = fold_segments(s_seg);
+    if ((lane & 7) == 0)
+        seg_out[(lane >> 3) * kWaves + wave] = (double)a1;
 }
 
 // ---- bin selection by one wavefront ----------------------------------------------------------------
@@ -741,151 +1051,229 @@ __device__ void block_sum2_f64(double& a, double& b, double* scratch /* 2 kWaves
     }
 }
 
-// ---- kernel 2: cut bins, exact masses, candidates; last workgroup of a row: threshold and walk ----------
-struct SelectLds {
+// ---- kernel 2: the row-level step ---------------------------------------------------------------------
+struct FinishLds {
     RowLds row;                           // hist / scratch / seg_mass of the row routines
-    unsigned long long cand[kCandCap];    // candidates of the row (last workgroup only)
-    double smass[kMaxSlices];
-    double sabove[kMaxSlices];
+    unsigned long long cand[kCandCap];    // candidates: logit bits | index << 32
+    double srest[kMaxSlices];             // estimated mass past the slice's window, relative to the row maximum
+    double spair[kMaxSlices];             // exact mass of the slice's pairs, relative to the slice maximum
+    double sfac[kMaxSlices];              // 2^((slice max - row max) c)
     float smax[kMaxSlices];
     int sarg[kMaxSlices];
     int shift[kMaxSlices];
-    int wave_cnt[kWaves];
-    unsigned cand_base;
-    unsigned arrived_before;
+    int swin_lo[kMaxSlices], swin_hi[kMaxSlices], scount[kMaxSlices];
+    int covered[kMaxSlices];
+    unsigned cand_total;
     uint32_t kmin[kWaves], kmax[kWaves];
 };
 
-// Estimate of the nucleus cut from the slices' histograms: the candidate bins [lo, hi] of the
-// row, counted down from the bin of the row maximum.  Called by a whole workgroup; L.smax
-// holds the slice maxima.  The arithmetic depends only on the row's data, so every workgroup
-// that evaluates it for a row gets the same bins.
-struct CutBins {
-    int lo, hi;
-};
-
-__device__ __forceinline__ CutBins estimate_cut(SelectLds& L, const RowWs& W, int slices, float kf_row, const RowConst& rc,
-                                float top_p)
+__global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
 {
-    const int tid = threadIdx.x;
-    int lo, hi;
-    if (tid < slices)
-        L.shift[tid] = L.smax[tid] == -INFINITY
-                           ? kBins
-                           : (int)fminf(fmaxf(kf_row - bin_coord(L.smax[tid], rc.c16), 0.f), (float)kBins);
-    __syncthreads();
-    // Bin b of slice s is bin b + shift[s] of the row; its mass is q 2^-15 2^(-bin/16) relative
-    // to the reference of the row maximum's bin.  Thread t gathers row bins 4 t .. 4 t + 3
-    // (all loads of eight slices are requested before any is used).
-    const int rb0 = kBinsPerThread * tid;
-    unsigned long long qsum[kBinsPerThread];
-#pragma unroll
-    for (int k = 0; k < kBinsPerThread; ++k)
-        qsum[k] = 0ull;
-    for (int s0 = 0; s0 < slices; s0 += 8) {
-        // unconditional loads from clamped positions (a guarded load would be waited for on
-        // the spot); what lies outside a slice's published bins is masked afterwards
-        unsigned qv[8][kBinsPerThread];
-        int sh[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int sl = min(s0 + u, slices - 1);
-            sh[u] = s0 + u < slices ? L.shift[sl] : kBins;
-#pragma unroll
-            for (int k = 0; k < kBinsPerThread; ++k) {
-                const int b = min(max(rb0 + k - sh[u], 0), kPubBins - 1);
-                qv[u][k] = W.hist[(size_t)sl * kPubBins + b];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-            for (int k = 0; k < kBinsPerThread; ++k) {
-                const int b = rb0 + k - sh[u];
-                qsum[k] += (b >= 0 && b < kPubBins) ? qv[u][k] : 0u;
-            }
-    }
-#pragma unroll
-    for (int k = 0; k < kBinsPerThread; ++k) {
-        const int rb = rb0 + k;
-        // 2^(-(rb mod 16)/16) in fp32 (an estimate is all that is needed), 2^(-15 - rb/16) as
-        // an exponent
-        const double root = (double)__builtin_amdgcn_exp2f(-0.0625f * (float)(rb & 15));
-        const double pow2 = __hiloint2double((1023 - 15 - (rb >> 4)) << 20, 0);
-        L.row.hist[rank_slot(rb)] = (double)qsum[k] * root * pow2;
-    }
-    __syncthreads();
-    const BinPick est = wave_pick(L.row.hist, 0.0, (double)top_p, true);
-    // the estimate is good to about 1e-5 of the total; be generous
-    const double need_est = (double)top_p * est.total, tol = 1e-3 * est.total;
-    lo = hi = est.bin;
-    if (need_est - est.above <= tol && lo > 0)
-        --lo;
-    if (est.above + est.in_bin - need_est <= tol && hi < kBins - 1)
-        ++hi;
-    __syncthreads();  // the histogram array is reused below
-    CutBins c;
-    c.lo = lo;
-    c.hi = hi;
-    return c;
-}
-
-// ---- optional kernel between the two: the row's cut bins, once per row ------------------------------
-// Used when a launch has so many workgroups that recomputing the estimate in each of them
-// would cost more than one more small kernel.
-__global__ __launch_bounds__(kBlock) void sampler_cut_kernel(SamplerParams sp, char* ws, int slices)
-{
-    __shared__ SelectLds L;
-    const int tid = threadIdx.x;
+    __shared__ FinishLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long r = blockIdx.x;
     const RowWs W = row_ws(ws, r, slices);
-    const float T = sp.temperature[r];
-    const float top_p = sp.top_p[r];
-    if (T == 0.f || !(top_p < 1.f))
-        return;
-    if (tid < slices)
-        L.smax[tid] = stat_at(W, tid)->max_x;
-    __syncthreads();
-    float M = -INFINITY;
-    for (int s = 0; s < slices; ++s)
-        M = fmaxf(M, L.smax[s]);
-    const RowConst rc = row_const(T);
-    const CutBins cb = estimate_cut(L, W, slices, bin_coord(M, rc.c16), rc, top_p);
-    if (tid == 0) {
-        W.ctl->lo = cb.lo;
-        W.ctl->hi = cb.hi;
-    }
-}
-
-// ---- exact threshold among the candidates, CDF walk: one workgroup per row -----------------------------
-// Runs in the workgroup of a row that finished last (select kernel) or in a kernel of its own.
-__device__ __forceinline__ void finish_row(SelectLds& L, const SamplerParams& sp, long long r, const RowWs& W,
-                                           int slices, int slice_elems, const RowScale& rs, const RowConst& rc,
-                                           float kf_row, int lo, int hi, bool cut, float top_p)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* __restrict__ x = sp.logits + r * sp.stride;
     const int V = (int)sp.vocab;
-    const unsigned cand_total = observe(&W.ctl->cand_total);
-    const int C = (int)min(cand_total, (unsigned)kCandCap);
+    const float T = sp.temperature[r];
+    const float top_p = sp.top_p[r];
+    const bool greedy = (T == 0.f);
+    const bool cut = !greedy && top_p < 1.f;
     const int nseg = slices * kSegPerSlice;
     double* seg_mass = L.row.seg_mass;
+
     if (tid < slices) {
         const SliceStat* st = stat_at(W, tid);
-        L.smass[tid] = observe(&st->mass);
-        L.sabove[tid] = observe(&st->above);
+        L.smax[tid] = st->max_x;
+        L.sarg[tid] = st->argmax;
+        if (!greedy) {
+            L.srest[tid] = st->rest;
+            L.spair[tid] = st->pair_mass;
+            L.swin_lo[tid] = st->win_lo;
+            L.swin_hi[tid] = st->win_hi;
+            L.scount[tid] = st->count;
+        }
     }
-    for (int i = tid; i < C; i += kBlock)
-        L.cand[i] = observe(&W.cand[i]);
-    for (int sidx = tid; sidx < nseg; sidx += kBlock)
-        seg_mass[sidx] = observe(&W.seg[sidx]);
+    if (tid == 0)
+        L.cand_total = 0u;
     __syncthreads();
-    double S = 0.0, above_total = 0.0;
+    float M = -INFINITY;
+    int arg = 0x7fffffff;
     for (int s = 0; s < slices; ++s) {
-        S += L.smass[s];
-        above_total += L.sabove[s];
+        if (L.smax[s] > M || (L.smax[s] == M && L.sarg[s] < arg)) {
+            M = L.smax[s];
+            arg = L.sarg[s];
+        }
     }
-    const double need = (double)top_p * S;
+    if (greedy) {
+        if (tid == 0)
+            sp.tokens[r] = arg == 0x7fffffff ? 0 : arg;
+        return;
+    }
+    const RowConst rc = row_const(T);
+    RowScale rs;
+    rs.max_x = M;
+    rs.c_hi = rc.c_hi;
+    rs.c_lo = rc.c_lo;
+    const float kf_row = bin_coord(M, rc.c16);
+    if (tid < slices) {
+        const bool empty = L.smax[tid] == -INFINITY;
+        L.shift[tid] = empty ? kBins : (int)fminf(fmaxf(kf_row - bin_coord(L.smax[tid], rc.c16), 0.f), (float)kBins);
+        L.sfac[tid] = empty ? 0.0 : exp2(((double)L.smax[tid] - (double)M) * rc.cd);
+        // the slice's histogram units refer to 2^(bin_coord(slice max) / 16); the row maximum is 2^(M c16 / 16)
+        L.srest[tid] = empty ? 0.0
+                             : L.srest[tid] * exp2(((double)bin_coord(L.smax[tid], rc.c16) - (double)M * (double)rc.c16) * 0.0625);
+    }
+    __syncthreads();
+
+    int lo = kBins, hi = kBins;  // candidate bins, counted down from the maximum's bin; kBins = no cut
+    if (cut) {
+        // Estimate of the nucleus cut from the slices' histograms.  Bin b of slice s is bin
+        // b + shift[s] of the row; thread t gathers row bins 4 t .. 4 t + 3 (all loads of eight
+        // slices are requested before any is used; loads are unconditional from clamped
+        // positions, what lies outside a slice's bins is masked afterwards).
+        const int rb0 = kBinsPerThread * tid;
+        unsigned long long qsum[kBinsPerThread];
+#pragma unroll
+        for (int k = 0; k < kBinsPerThread; ++k)
+            qsum[k] = 0ull;
+        for (int s0 = 0; s0 < slices; s0 += 8) {
+            unsigned qv[8][kBinsPerThread];
+            int sh[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int sl = min(s0 + u, slices - 1);
+                sh[u] = s0 + u < slices ? L.shift[sl] : kBins;
+#pragma unroll
+                for (int k = 0; k < kBinsPerThread; ++k) {
+                    const int b = min(max(rb0 + k - sh[u], 0), kPubBins - 1);
+                    qv[u][k] = W.hist[(size_t)sl * kPubBins + b];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int k = 0; k < kBinsPerThread; ++k) {
+                    const int b = rb0 + k - sh[u];
+                    qsum[k] += (b >= 0 && b < kPubBins) ? qv[u][k] : 0u;
+                }
+        }
+#pragma unroll
+        for (int k = 0; k < kBinsPerThread; ++k)
+            L.row.hist[rank_slot(rb0 + k)] = (double)qsum[k] * bin_unit(rb0 + k);
+        __syncthreads();
+        const BinPick est = wave_pick(L.row.hist, 0.0, (double)top_p, true);
+        // the estimate is good to about 1e-5 of the total; be generous
+        const double need_est = (double)top_p * est.total, tol = 1e-3 * est.total;
+        lo = hi = est.bin;
+        if (need_est - est.above <= tol && lo > 0)
+            --lo;
+        if (est.above + est.in_bin - need_est <= tol && hi < kBins - 1)
+            ++hi;
+        __syncthreads();  // the histogram array is reused below
+    }
+    // A slice is covered when its emitted bins contain the row's cut bins and everything it summed
+    // as above its window is above `lo` (bin b of the slice is bin b + shift of the row).
+    if (tid < slices) {
+        bool ok = true;
+        if (cut) {
+            const int a = L.swin_lo[tid], z = L.swin_hi[tid], sh = L.shift[tid];
+            ok = L.scount[tid] >= 0 && z >= 0 && (a == 0 || a + sh <= lo) && (z >= kPubBins - 1 || hi <= z + sh);
+        }
+        L.covered[tid] = ok ? 1 : 0;
+    }
+    __syncthreads();
+    // Bin tests without forming the bin (see the scan kernel): lo == kBins keeps everything,
+    // hi == kBins - 1 makes every remaining element a candidate.
+    const float t_above = lo >= kBins ? -INFINITY : kf_row - (float)lo + 1.f;
+    const float t_cand = hi >= kBins - 1 ? -INFINITY : kf_row - (float)hi;
+
+    // ---- mass kept for certain, per 256-element segment in vocabulary order; candidates ----------------
+    // The row mass S is put together on the way: exact for the pairs of the covered slices (summed
+    // by the scan kernel), for what those slices summed above their windows and for every logit of
+    // the slices read a second time; estimated from the histograms for the bins past the windows.
+    double s_part = 0.0;
+    for (int sidx = tid; sidx < nseg; sidx += kBlock) {
+        const int s = sidx / kSegPerSlice;
+        const double v = L.covered[s] ? W.seg[sidx] * L.sfac[s] : 0.0;
+        seg_mass[sidx] = v;
+        s_part += v;
+    }
+    if (cut && tid < slices && L.covered[tid])
+        s_part += L.srest[tid] + L.spair[tid] * L.sfac[tid];
+    __syncthreads();
+    // One element: kept for certain -> its segment; inside the cut bins -> the candidate list (the
+    // lanes of a wavefront take consecutive places reserved with one counter update); else dropped.
+    // Called by whole wavefronts (`live` masks lanes that hold nothing).
+    float f_part = 0.f;  // exact mass of the elements taken since the last widening
+    auto take = [&](auto whole_mass, bool live, float xq, int idx, int s) __attribute__((always_inline)) {
+        const float t = xq * rc.c16;
+        const bool above = live && t >= t_above;
+        const bool candq = live && !above && t >= t_cand;
+        if (decltype(whole_mass)::value)
+            f_part += live ? prob(xq, rs) : 0.f;  // a second look adds up the slice's mass itself
+        if (above)
+            atomicAdd(&seg_mass[s * kSegPerSlice + (idx - s * slice_elems) / kSeg], (double)prob(xq, rs));
+        const unsigned long long mask = __ballot(candq);
+        if (mask != 0ull) {
+            unsigned base = 0u;
+            if (lane == 0)
+                base = atomicAdd(&L.cand_total, (unsigned)__popcll(mask));
+            base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+            if (candq) {
+                const unsigned pos = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+                if (pos < (unsigned)kCandCap)
+                    L.cand[pos] = (unsigned long long)__float_as_uint(xq) | ((unsigned long long)(unsigned)idx << 32);
+            }
+        }
+    };
+    // pairs written out by the covered slices: four per thread and slice, all requested before any is
+    // used (unconditional loads from clamped positions; what lies past a slice's count is masked)
+    static_assert(kEmitCap == 4 * kBlock, "four pairs per thread and slice");
+    for (int s0 = 0; s0 < slices; s0 += 4) {
+        unsigned long long ev[4][4];
+        int cnt[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = min(s0 + u, slices - 1);
+            cnt[u] = (s0 + u < slices && L.covered[s]) ? min(L.scount[s], kEmitCap) : 0;
+            const unsigned long long* e = W.emit + (size_t)s * kEmitCap;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                ev[u][k] = e[tid + k * kBlock];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                take(std::false_type{}, tid + k * kBlock < cnt[u], __uint_as_float((unsigned)ev[u][k]),
+                     (int)(ev[u][k] >> 32), min(s0 + u, slices - 1));
+    }
+    // slices that are not covered: a second look at their logits
+    for (int s = 0; s < slices; ++s) {
+        if (L.covered[s])
+            continue;
+        const SliceRange g = slice_range(s, slice_elems, V);
+        float xv[32];
+        SPD_LOAD_SLICE(xv, x, g, tid)
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            const int i = g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3);
+            take(std::true_type{}, i < g.v4end, xv[q], i, s);
+        }
+        for (int k = 0; k < 3; ++k)
+            take(std::true_type{}, tid == 0 && k < g.ntail, tid == 0 && k < g.ntail ? x[g.v4end + k] : 0.f, g.v4end + k, s);
+        s_part += (double)f_part;
+        f_part = 0.f;
+    }
+    __syncthreads();
+    const unsigned cand_total = L.cand_total;
+    const int C = (int)min(cand_total, (unsigned)kCandCap);
+    double above_total = 0.0;
+    for (int sidx = tid; sidx < nseg; sidx += kBlock)
+        above_total += seg_mass[sidx];
+    block_sum2_f64(above_total, s_part, L.row.scratch);
+    const double need = (double)top_p * s_part;  // s_part: the row mass S
 
     uint32_t key_tau = 0u;
     double Z = above_total;
@@ -960,14 +1348,6 @@ __device__ __forceinline__ void finish_row(SelectLds& L, const SamplerParams& sp
         }
     }
     __syncthreads();
-    if (!cut) {
-        // Nothing is cut: the normaliser is the sum of the segments as they stand now, i.e. with the
-        // row's last one to three logits (which travel as candidates) included.
-        double part = 0.0;
-        for (int sidx = tid; sidx < nseg; sidx += kBlock)
-            part += seg_mass[sidx];
-        Z = block_sum_f64(part, L.row.scratch);
-    }
     const double target = (double)sp.uniforms[r] * Z;
 
     if (wave == 0) {
@@ -1068,249 +1448,6 @@ __device__ __forceinline__ void finish_row(SelectLds& L, const SamplerParams& sp
     }
 }
 
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void sampler_select_kernel(SamplerParams sp, char* ws, int slices,
-                                                                int slice_elems, int cut_ready)
-{
-    __shared__ SelectLds L;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long r = blockIdx.x / slices;
-    const int slice = blockIdx.x % slices;
-    const RowWs W = row_ws(ws, r, slices);
-    const float* __restrict__ x = sp.logits + r * sp.stride;
-    const int V = (int)sp.vocab;
-    const SliceRange g = slice_range(slice, slice_elems, V);
-    const float T = sp.temperature[r];
-    const bool greedy = (T == 0.f);
-    const float top_p = sp.top_p[r];
-    const bool cut = !greedy && top_p < 1.f;
-
-    // The slice statistics are requested first and the slice's logits right behind them (loads
-    // return in order); the row's cut is worked out while the logits travel.
-    float st_max = -INFINITY;
-    int st_arg = 0x7fffffff;
-    int lo = kBins, hi = kBins;  // candidate bins, counted down from the maximum's bin; kBins = no cut
-    if (cut && cut_ready) {
-        lo = W.ctl->lo;
-        hi = W.ctl->hi;
-    }
-    if (tid < slices) {
-        const SliceStat* st = stat_at(W, tid);
-        st_max = st->max_x;
-        st_arg = st->argmax;
-    }
-    float xv[32];
-    {
-        // a greedy row needs no second look: all its loads collapse onto one float4
-        SliceRange gl = g;
-        if (greedy)
-            gl.v4end = gl.e0 + 4;
-        SPD_LOAD_SLICE(xv, x, gl, tid)
-    }
-    if (tid < slices) {
-        L.smax[tid] = st_max;
-        L.sarg[tid] = st_arg;
-    }
-    __syncthreads();
-    float M = -INFINITY;
-    int arg = 0x7fffffff;
-    for (int s = 0; s < slices; ++s) {
-        if (L.smax[s] > M || (L.smax[s] == M && L.sarg[s] < arg)) {
-            M = L.smax[s];
-            arg = L.sarg[s];
-        }
-    }
-    if (greedy) {
-        if (slice == 0 && tid == 0)
-            sp.tokens[r] = arg == 0x7fffffff ? 0 : arg;
-        return;
-    }
-    const RowConst rc = row_const(T);
-    const float kf_row = bin_coord(M, rc.c16);
-    if (cut && !cut_ready) {
-        const CutBins cb = estimate_cut(L, W, slices, kf_row, rc, top_p);
-        lo = cb.lo;
-        hi = cb.hi;
-    }
-
-    SPD_MASK_SLICE(xv, g, tid)
-    RowScale rs;
-    rs.max_x = M;
-    rs.c_hi = rc.c_hi;
-    rs.c_lo = rc.c_lo;
-    // Bin tests without forming the bin: with t = x c16, bin(x) < lo  <=>  floor(t) > kf_row - lo
-    // <=>  t >= kf_row - lo + 1 (both sides of the middle inequality are integers); likewise
-    // bin(x) <= hi  <=>  t >= kf_row - hi.  The clamps of the bin only matter at the ends:
-    // lo == kBins keeps everything, hi == kBins - 1 makes every remaining element a candidate.
-    const float t_above = lo >= kBins ? -INFINITY : kf_row - (float)lo + 1.f;
-    const float t_cand = hi >= kBins - 1 ? -INFINITY : kf_row - (float)hi;
-
-    int ncand = 0;
-    double above = 0.0;
-    float all32 = 0.f;  // this thread's 32 probabilities; widened once
-    float s_above[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        s_above[j] = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float xq = xv[4 * j + k];
-            if (xq == -INFINITY)
-                continue;
-            const float pq = prob(xq, rs);
-            all32 += pq;
-            const float t = xq * rc.c16;
-            if (t >= t_above)
-                s_above[j] += pq;
-            else if (t >= t_cand)
-                ++ncand;
-        }
-    }
-    // 256 fp32 terms per segment.  The eight wavefront reductions are folded: after the exchange
-    // across 32 lanes each half keeps four segments, then two, then one, so that lane 8 s ends
-    // up with the sum of segment s (10 exchanges instead of 48).
-    {
-        const bool up32 = (lane & 32) != 0, up16 = (lane & 16) != 0, up8 = (lane & 8) != 0;
-        float a4[4], a2[2], a1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float keep = up32 ? s_above[4 + j] : s_above[j];
-            const float give = up32 ? s_above[j] : s_above[4 + j];
-            a4[j] = keep + __shfl_xor(give, 32);
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float keep = up16 ? a4[2 + j] : a4[j];
-            const float give = up16 ? a4[j] : a4[2 + j];
-            a2[j] = keep + __shfl_xor(give, 16);
-        }
-        {
-            const float keep = up8 ? a2[1] : a2[0];
-            const float give = up8 ? a2[0] : a2[1];
-            a1 = keep + __shfl_xor(give, 8);
-        }
-        a1 += __shfl_xor(a1, 4);
-        a1 += __shfl_xor(a1, 2);
-        a1 += __shfl_xor(a1, 1);
-        // lane 8 s (and its seven neighbours) holds segment j = 4 (lane/32) + 2 (lane/16 % 2) + lane/8 % 2
-        if ((lane & 7) == 0) {
-            const int j = lane >> 3;
-            publish(&W.seg[(size_t)slice * kSegPerSlice + j * kWaves + wave], (double)a1, cut_ready != 0);
-            above = (double)a1;
-        }
-    }
-    double mass = (double)all32;
-    // tail logits (thread 0): counted in the slice mass, always sent as candidates when kept at all
-    int tail_cand = 0;
-    if (tid == 0)
-        for (int k = 0; k < g.ntail; ++k) {
-            const float xt = x[g.v4end + k];
-            mass += (double)prob(xt, rs);
-            if (bin_below(kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins)
-                ++tail_cand;
-        }
-    ncand += tail_cand;
-    block_sum2_f64(mass, above, L.row.scratch);
-
-    int incl = ncand;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(incl, o);
-        if (lane >= o)
-            incl += up;
-    }
-    __syncthreads();
-    if (lane == 63)
-        L.wave_cnt[wave] = incl;
-    __syncthreads();
-    int wave_off = 0, block_total = 0;
-    for (int w = 0; w < kWaves; ++w) {
-        if (w < wave)
-            wave_off += L.wave_cnt[w];
-        block_total += L.wave_cnt[w];
-    }
-    if (tid == 0) {
-        L.cand_base = block_total ? __hip_atomic_fetch_add(&W.ctl->cand_total, (unsigned)block_total,
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                  : 0u;
-        SliceStat* st = stat_at(W, slice);
-        publish(&st->mass, mass, cut_ready != 0);
-        publish(&st->above, above, cut_ready != 0);
-    }
-    __syncthreads();
-    if (ncand) {
-        unsigned pos = L.cand_base + (unsigned)(wave_off + incl - ncand);
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const float xq = xv[q];
-            if (xq == -INFINITY)
-                continue;
-            const float t = xq * rc.c16;
-            if (t < t_above && t >= t_cand) {
-                if (pos < (unsigned)kCandCap)
-                    publish(&W.cand[pos],
-                            (unsigned long long)__float_as_uint(xq) |
-                                ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32),
-                            cut_ready != 0);
-                ++pos;
-            }
-        }
-        if (tid == 0)
-            for (int k = 0; k < g.ntail; ++k) {
-                const float xt = x[g.v4end + k];
-                if (bin_below(kf_row, bin_coord(xt, rc.c16)) <= hi || lo == kBins) {
-                    if (pos < (unsigned)kCandCap)
-                        publish(&W.cand[pos], (unsigned long long)__float_as_uint(xt) |
-                                                  ((unsigned long long)(unsigned)(g.v4end + k) << 32),
-                                cut_ready != 0);
-                    ++pos;
-                }
-            }
-    }
-
-    if (cut_ready)
-        return;  // many workgroups per launch: the pick kernel finishes the rows
-
-    // ---- arrival: everything this workgroup published has been acknowledged before it counts ----
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0)
-        L.arrived_before = __hip_atomic_fetch_add(&W.ctl->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (L.arrived_before != (unsigned)(slices - 1))
-        return;
-    // last workgroup of the row
-    finish_row(L, sp, r, W, slices, slice_elems, rs, rc, kf_row, lo, hi, cut, top_p);
-}
-
-// The finishing step as a kernel of its own, for launches with many workgroups: there the select
-// kernel's workgroups neither wait for their stores to be acknowledged nor count arrivals.
-__global__ __launch_bounds__(kBlock) void sampler_pick_kernel(SamplerParams sp, char* ws, int slices,
-                                                              int slice_elems)
-{
-    __shared__ SelectLds L;
-    const int tid = threadIdx.x;
-    const long long r = blockIdx.x;
-    const RowWs W = row_ws(ws, r, slices);
-    const float T = sp.temperature[r];
-    if (T == 0.f)
-        return;  // greedy rows were answered by the select kernel
-    const float top_p = sp.top_p[r];
-    const bool cut = top_p < 1.f;
-    if (tid < slices)
-        L.smax[tid] = stat_at(W, tid)->max_x;
-    __syncthreads();
-    float M = -INFINITY;
-    for (int s = 0; s < slices; ++s)
-        M = fmaxf(M, L.smax[s]);
-    const RowConst rc = row_const(T);
-    RowScale rs;
-    rs.max_x = M;
-    rs.c_hi = rc.c_hi;
-    rs.c_lo = rc.c_lo;
-    const int lo = cut ? W.ctl->lo : kBins, hi = cut ? W.ctl->hi : kBins;
-    finish_row(L, sp, r, W, slices, slice_elems, rs, rc, bin_coord(M, rc.c16), lo, hi, cut, top_p);
-}
-
-
 __global__ __launch_bounds__(kBlock) void sample_rows_kernel(SamplerParams sp)
 {
     __shared__ RowLds lds;
@@ -1325,9 +1462,8 @@ int sampler_slices(long long rows, long long vocab)
     const long long smin = (vocab + kSliceMax - 1) / kSliceMax;
     if (smin > kMaxSlices)
         return 0;  // whole-row kernel
-    // Two workgroups per CU, but no more than eight slices unless the vocabulary needs them (every
-    // workgroup of a row re-reads all the row's slice histograms: measured 42 / 60 / 76 us with
-    // 8 / 12 / 16 slices on 64 rows of 128256), and no slice shorter than 4096 logits.
+    // Two workgroups per CU, at most eight slices unless the vocabulary needs more (the row-level
+    // step reads every slice's histogram), and no slice shorter than 4096 logits.
     long long s = (512 + rows - 1) / rows;
     const long long smax_small = vocab / 4096 > 1 ? vocab / 4096 : 1;
     if (s > smax_small) s = smax_small;
@@ -1352,20 +1488,10 @@ hipError_t launch_sampler(const SamplerParams& p, void* ws, hipStream_t s)
     }
     int slice_elems = (int)((p.vocab + slices - 1) / slices);
     slice_elems = (slice_elems + 3) / 4 * 4;
-    const dim3 per_slice((unsigned)(p.rows * slices)), block(kBlock);
-    hipLaunchKernelGGL(sampler_hist_kernel, per_slice, block, 0, s, p, (char*)ws, slices, slice_elems);
-    // With many workgroups per launch the cut estimate is computed once per row instead of in
-    // every workgroup of the row, and the rows are finished by a kernel of their own: four
-    // kernels whose workgroups are short, instead of two whose workgroups wait on one another's
-    // results.
-    const int cut_ready = p.rows * slices > 2048 ? 1 : 0;
-    if (cut_ready)
-        hipLaunchKernelGGL(sampler_cut_kernel, dim3((unsigned)p.rows), block, 0, s, p, (char*)ws, slices);
-    hipLaunchKernelGGL(sampler_select_kernel, per_slice, block, 0, s, p, (char*)ws, slices, slice_elems,
-                       cut_ready);
-    if (cut_ready)
-        hipLaunchKernelGGL(sampler_pick_kernel, dim3((unsigned)p.rows), block, 0, s, p, (char*)ws, slices,
-                           slice_elems);
+    hipLaunchKernelGGL(sampler_scan_kernel, dim3((unsigned)(p.rows * slices)), dim3(kBlock), 0, s, p, (char*)ws, slices,
+                       slice_elems);
+    hipLaunchKernelGGL(sampler_finish_kernel, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p, (char*)ws, slices,
+                       slice_elems);
     return hipGetLastError();
 }
 
