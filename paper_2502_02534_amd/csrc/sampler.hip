@@ -134,7 +134,7 @@ __device__ void pick_bin(const double* hist, double above, double need, int* bin
 // Shared-memory arrays of the row routines (one instance per workgroup).
 struct RowLds {
     double hist[kBins];
-    double scratch[kBlock];  // block sums and scans use the first kWaves entries
+    double scratch[2 * kWaves];  // block sums and scans
     double seg_mass[kMaxSegments];
     float red_f[kWaves];
     int red_i[kWaves];
@@ -446,7 +446,6 @@ struct SliceStat {
     float max_x;
     int argmax;
     double rest;      // estimated mass of the slice's bins past win_hi, in units of 2^(bin_coord(max_x) / 16)
-    double pair_mass; // sum of 2^((x - max_x) c) over the pairs written out
     int win_lo;       // emitted bins [win_lo, win_hi], counted down from the bin of max_x
     int win_hi;
     int count;        // emitted pairs; -1: the slice emitted nothing although the row has a cut
@@ -577,19 +576,21 @@ template <typename F> __device__ __forceinline__ int last_true(int lo_b, int hi_
 }
 
 // ---- kernel 1: the pass over the logits --------------------------------------------------------------
+constexpr int kWaveStage = kEmitCap / kWaves * 2;  // pairs one wavefront may gather (twice its even share)
+
 struct ScanLds {
-    unsigned hist[kPubBins];
+    unsigned hist[kPubBins + 64];       // + one place per lane for what lies past the last bin
     unsigned cumq[kPubBins];            // inclusive running sum of hist
-    unsigned long long stage[kEmitCap]; // the slice's list, gathered here and copied out in one piece
+    unsigned long long stage[kWaves][kWaveStage];  // each wavefront's pairs, copied out in one piece
     double wave_mass[kWaves];
     unsigned wave_q[kWaves];
     float red_f[kWaves];
     int red_i[kWaves];
     double rest;               // estimated mass of the bins past the window
-    double pair_mass[kWaves];  // exact mass of the pairs each wavefront gathered
     int cut_bin;               // the slice's own cut bin L
     int best;                  // scratch of the window search
     int emitted;               // places reserved in the slice's list so far
+    int overflow;              // some wavefront gathered more pairs than it has room for
 };
 
 // Barrier between phases that exchange data through LDS only: waits for this wavefront's LDS
@@ -601,7 +602,8 @@ __device__ __forceinline__ void lds_barrier()
 }
 
 // Fixed-point mass of a logit inside its bin: 32768 2^(f/16) for f in [0, 1), as a cubic in f
-// (the next term of the series is below 0.005 units).
+// (the next term of the series is below 0.005 units).  NaN (positions past the end of a slice)
+// converts to 0.
 __device__ __forceinline__ unsigned bin_units(float f)
 {
     const float a1 = 1419.5653f, a2 = 30.749034f, a3 = 0.44403f;
@@ -646,7 +648,7 @@ __device__ __forceinline__ float fold_segments(const float (&s_seg)[8])
     return a1;  // lanes 8 s .. 8 s + 7 hold segment j = 4 (lane/32) + 2 (lane/16 % 2) + lane/8 % 2 = lane >> 3
 }
 
-__global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void sampler_scan_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
 {
     __shared__ ScanLds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -667,15 +669,16 @@ __global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, 
         for (int k = 0; k < 3; ++k)
             if (k < g.ntail)
                 tail[k] = x[g.v4end + k];
-    for (int b = tid; b < kPubBins; b += kBlock)
+    for (int b = tid; b < kPubBins + 64; b += kBlock)
         L.hist[b] = 0u;
     if (tid == 0) {
         L.cut_bin = kPubBins - 1;
         L.best = -1;
         L.emitted = 0;
+        L.overflow = 0;
         L.rest = 0.0;
     }
-    // wavefronts whose 32 x 64 x 4 logits all lie inside the slice skip the end-of-slice tests
+    // wavefronts whose 32 x 64 x 4 logits all lie inside the slice skip the end-of-slice masking
     const bool whole = g.e0 + 7 * kIter + (tid | 63) * 4 + 4 <= g.v4end;
     if (!whole) {
         SPD_MASK_SLICE(xv, g, tid)
@@ -751,7 +754,6 @@ __global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, 
             st->max_x = mx;
             st->argmax = 0;
             st->rest = 0.0;
-            st->pair_mass = 0.0;
             st->win_lo = 0;
             st->win_hi = -1;
             st->count = n;
@@ -760,37 +762,31 @@ __global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, 
     }
 
     // ---- histogram of mass over the slice's own bins.  Elements 64 octaves and more below the slice
-    // maximum share the last bin; they are counted per thread and added once (they would otherwise
-    // all meet at one LDS address). ----
-    unsigned far_units = 0u;
+    // maximum belong to the last bin; each lane collects them in a place of its own (they would
+    // otherwise all meet at one LDS address) and the places are added to the last bin afterwards.
+    // Positions past the end of the slice (-inf) land there too, with zero units. ----
+    const float far_slot = (float)(kPubBins + lane);
     auto bin_one = [&](float xq) __attribute__((always_inline)) {
         const float t = xq * rc.c16;
         const float kf = floorf(t);
         const float bf = kf_loc - kf;  // >= 0: kf_loc belongs to the maximum
-        const unsigned u = bin_units(t - kf);
-        if (bf < (float)(kPubBins - 1))
-            atomicAdd(&L.hist[(int)bf], u);
-        else
-            far_units += u;
+        atomicAdd(&L.hist[(int)(bf < (float)(kPubBins - 1) ? bf : far_slot)], bin_units(t - kf));
     };
-    if (whole) {
 #pragma unroll
-        for (int q = 0; q < 32; ++q)
-            bin_one(xv[q]);
-    } else {
-#pragma unroll
-        for (int q = 0; q < 32; ++q)
-            if (xv[q] != -INFINITY)
-                bin_one(xv[q]);
-    }
+    for (int q = 0; q < 32; ++q)
+        bin_one(xv[q]);
     for (int k = 0; k < 3; ++k)
         if (tail[k] != -INFINITY)
             bin_one(tail[k]);
-    for (int o = 32; o > 0; o >>= 1)
-        far_units += __shfl_xor(far_units, o);
-    if (lane == 0 && far_units)
-        atomicAdd(&L.hist[kPubBins - 1], far_units);
     lds_barrier();  // histogram complete
+    if (wave == 0) {
+        unsigned far_units = L.hist[kPubBins + lane];
+        for (int o = 32; o > 0; o >>= 1)
+            far_units += __shfl_xor(far_units, o);
+        if (lane == 0)
+            L.hist[kPubBins - 1] += far_units;
+    }
+    lds_barrier();
 
     // ---- running sums over the bins (thread t owns bins 2t, 2t+1): fixed-point units for the element
     // counts, estimated mass for the slice's own cut bin ----
@@ -878,81 +874,61 @@ __global__ __launch_bounds__(kBlock) void sampler_scan_kernel(SamplerParams sp, 
     const float t_above = win_lo <= 0 ? INFINITY : kf_loc - (float)win_lo + 1.f;
     const float t_emit = win_hi < 0 ? INFINITY : (win_hi >= kPubBins - 1 ? -3.0e38f : kf_loc - (float)win_hi);
 
-    // ---- places in the slice's list: count per thread, running count over the wavefront, one
-    // reservation per wavefront; the pairs are gathered in LDS and copied out in one piece ----
-    int nemit = 0;
+    // ---- the pairs: every wavefront gathers its own in LDS (the lanes that hold one take consecutive
+    // places), reserves as many places in the slice's list and copies them out in one piece ----
+    int have = 0;  // pairs this wavefront has gathered (uniform)
+    auto gather = [&](bool pred, float xq, int idx) __attribute__((always_inline)) {
+        const unsigned long long mask = __ballot(pred);
+        if (mask != 0ull) {
+            if (pred) {
+                const int pos = have + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                                       __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+                if (pos < kWaveStage)
+                    L.stage[wave][pos] = (unsigned long long)__float_as_uint(xq) | ((unsigned long long)(unsigned)idx << 32);
+            }
+            have += __popcll(mask);
+        }
+    };
     if (win_hi >= 0) {
         if (win_lo <= 0) {
 #pragma unroll
             for (int q = 0; q < 32; ++q)
-                nemit += xv[q] * rc.c16 >= t_emit ? 1 : 0;
+                gather(xv[q] * rc.c16 >= t_emit, xv[q], g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
         } else {
 #pragma unroll
             for (int q = 0; q < 32; ++q) {
                 const float t = xv[q] * rc.c16;
-                nemit += (t >= t_emit && t < t_above) ? 1 : 0;
-            }
-        }
-    }
-    bool tail_out[3];
-    for (int k = 0; k < 3; ++k) {
-        tail_out[k] = win_hi >= 0 && tail[k] * rc.c16 >= t_emit;  // (-inf where there is no tail logit)
-        nemit += tail_out[k] ? 1 : 0;
-    }
-    int incl = nemit;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(incl, o);
-        if (lane >= o)
-            incl += up;
-    }
-    int base = 0;
-    if (lane == 63 && incl)
-        base = atomicAdd(&L.emitted, incl);
-    base = __shfl(base, 63);
-    float pm = 0.f;  // exact mass of this thread's pairs
-    if (nemit) {
-        int pos = base + incl - nemit;
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const float t = xv[q] * rc.c16;
-            if (t >= t_emit && t < t_above) {
-                pm += prob(xv[q], rs);
-                if (pos < kEmitCap)
-                    L.stage[pos] = (unsigned long long)__float_as_uint(xv[q]) |
-                                   ((unsigned long long)(unsigned)(g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3)) << 32);
-                ++pos;
+                gather(t >= t_emit && t < t_above, xv[q], g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
             }
         }
         for (int k = 0; k < 3; ++k)
-            if (tail_out[k]) {
-                pm += prob(tail[k], rs);
-                if (pos < kEmitCap)
-                    L.stage[pos] = (unsigned long long)__float_as_uint(tail[k]) | ((unsigned long long)(unsigned)(g.v4end + k) << 32);
-                ++pos;
-            }
+            gather(tail[k] * rc.c16 >= t_emit, tail[k], g.v4end + k);  // (-inf where there is no tail logit)
     }
-    {
-        const double wm = wave_sum_f64((double)pm);
-        if (lane == 0)
-            L.pair_mass[wave] = wm;
+    int base = 0;
+    if (lane == 0 && have) {
+        base = atomicAdd(&L.emitted, have);
+        if (have > kWaveStage)
+            L.overflow = 1;
     }
+    base = __builtin_amdgcn_readfirstlane(base);
     lds_barrier();
-    const int total = min(L.emitted, kEmitCap);
+    // A wavefront that ran out of room (sorted logits can put a slice's whole window into one
+    // wavefront) makes the slice publish nothing: the row-level step then reads it a second time.
+    const bool publish = win_hi >= 0 && !L.overflow;
+    const int total = L.emitted;
     if (tid == 0) {
         SliceStat* st = stat_at(W, slice);
         st->max_x = mx;
         st->argmax = 0;
         st->rest = L.rest;
-        double pmass = 0.0;
-        for (int w = 0; w < kWaves; ++w)
-            pmass += L.pair_mass[w];
-        st->pair_mass = pmass;
         st->win_lo = win_lo;
-        st->win_hi = win_hi;
-        st->count = win_hi < 0 ? -1 : total;
+        st->win_hi = publish ? win_hi : -1;
+        st->count = publish ? total : -1;
     }
-    for (int i = tid; i < total; i += kBlock)
-        out[i] = L.stage[i];
+    if (publish)
+        for (int i = lane; i < min(have, kWaveStage); i += 64)
+            if (base + i < kEmitCap)
+                out[base + i] = L.stage[wave][i];
     *reinterpret_cast<uint2*>(&W.hist[(size_t)slice * kPubBins + 2 * tid]) = make_uint2(q0, q1);
     // ---- segment sums: what lies above the window (nothing when the window starts at the top) ----
     float s_seg[8];
@@ -1056,7 +1032,6 @@ struct FinishLds {
     RowLds row;                           // hist / scratch / seg_mass of the row routines
     unsigned long long cand[kCandCap];    // candidates: logit bits | index << 32
     double srest[kMaxSlices];             // estimated mass past the slice's window, relative to the row maximum
-    double spair[kMaxSlices];             // exact mass of the slice's pairs, relative to the slice maximum
     double sfac[kMaxSlices];              // 2^((slice max - row max) c)
     float smax[kMaxSlices];
     int sarg[kMaxSlices];
@@ -1088,7 +1063,6 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
         L.sarg[tid] = st->argmax;
         if (!greedy) {
             L.srest[tid] = st->rest;
-            L.spair[tid] = st->pair_mass;
             L.swin_lo[tid] = st->win_lo;
             L.swin_hi[tid] = st->win_hi;
             L.scount[tid] = st->count;
@@ -1189,9 +1163,9 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     const float t_cand = hi >= kBins - 1 ? -INFINITY : kf_row - (float)hi;
 
     // ---- mass kept for certain, per 256-element segment in vocabulary order; candidates ----------------
-    // The row mass S is put together on the way: exact for the pairs of the covered slices (summed
-    // by the scan kernel), for what those slices summed above their windows and for every logit of
-    // the slices read a second time; estimated from the histograms for the bins past the windows.
+    // The row mass S is put together on the way: exact for every element this kernel sees (the pairs
+    // of the covered slices, every logit of the others) and for what the covered slices summed above
+    // their windows, estimated from the histograms for the bins past the windows.
     double s_part = 0.0;
     for (int sidx = tid; sidx < nseg; sidx += kBlock) {
         const int s = sidx / kSegPerSlice;
@@ -1200,20 +1174,22 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
         s_part += v;
     }
     if (cut && tid < slices && L.covered[tid])
-        s_part += L.srest[tid] + L.spair[tid] * L.sfac[tid];
+        s_part += L.srest[tid];
     __syncthreads();
     // One element: kept for certain -> its segment; inside the cut bins -> the candidate list (the
     // lanes of a wavefront take consecutive places reserved with one counter update); else dropped.
     // Called by whole wavefronts (`live` masks lanes that hold nothing).
     float f_part = 0.f;  // exact mass of the elements taken since the last widening
-    auto take = [&](auto whole_mass, bool live, float xq, int idx, int s) __attribute__((always_inline)) {
+    auto take = [&](bool live, float xq, int idx, int s) __attribute__((always_inline)) {
+        if (__ballot(live) == 0ull)
+            return;  // nothing in this wavefront's 64 places
         const float t = xq * rc.c16;
         const bool above = live && t >= t_above;
         const bool candq = live && !above && t >= t_cand;
-        if (decltype(whole_mass)::value)
-            f_part += live ? prob(xq, rs) : 0.f;  // a second look adds up the slice's mass itself
+        const float pq = live ? prob(xq, rs) : 0.f;
+        f_part += pq;
         if (above)
-            atomicAdd(&seg_mass[s * kSegPerSlice + (idx - s * slice_elems) / kSeg], (double)prob(xq, rs));
+            atomicAdd(&seg_mass[s * kSegPerSlice + (idx - s * slice_elems) / kSeg], (double)pq);
         const unsigned long long mask = __ballot(candq);
         if (mask != 0ull) {
             unsigned base = 0u;
@@ -1230,11 +1206,11 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     // pairs written out by the covered slices: four per thread and slice, all requested before any is
     // used (unconditional loads from clamped positions; what lies past a slice's count is masked)
     static_assert(kEmitCap == 4 * kBlock, "four pairs per thread and slice");
-    for (int s0 = 0; s0 < slices; s0 += 4) {
-        unsigned long long ev[4][4];
-        int cnt[4];
+    for (int s0 = 0; s0 < slices; s0 += 8) {
+        unsigned long long ev[8][4];
+        int cnt[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
             const int s = min(s0 + u, slices - 1);
             cnt[u] = (s0 + u < slices && L.covered[s]) ? min(L.scount[s], kEmitCap) : 0;
             const unsigned long long* e = W.emit + (size_t)s * kEmitCap;
@@ -1243,11 +1219,13 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
                 ev[u][k] = e[tid + k * kBlock];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                take(std::false_type{}, tid + k * kBlock < cnt[u], __uint_as_float((unsigned)ev[u][k]),
-                     (int)(ev[u][k] >> 32), min(s0 + u, slices - 1));
+                take(tid + k * kBlock < cnt[u], __uint_as_float((unsigned)ev[u][k]), (int)(ev[u][k] >> 32),
+                     min(s0 + u, slices - 1));
+        s_part += (double)f_part;
+        f_part = 0.f;
     }
     // slices that are not covered: a second look at their logits
     for (int s = 0; s < slices; ++s) {
@@ -1259,10 +1237,10 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
 #pragma unroll
         for (int q = 0; q < 32; ++q) {
             const int i = g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3);
-            take(std::true_type{}, i < g.v4end, xv[q], i, s);
+            take(i < g.v4end, xv[q], i, s);
         }
         for (int k = 0; k < 3; ++k)
-            take(std::true_type{}, tid == 0 && k < g.ntail, tid == 0 && k < g.ntail ? x[g.v4end + k] : 0.f, g.v4end + k, s);
+            take(tid == 0 && k < g.ntail, tid == 0 && k < g.ntail ? x[g.v4end + k] : 0.f, g.v4end + k, s);
         s_part += (double)f_part;
         f_part = 0.f;
     }
