@@ -4,8 +4,7 @@
 // neither needs the other's result before the merge.  One grid of 256-thread workgroups with
 // 80 KB of LDS carries both, two workgroups per CU: the first workgroups run the prefix body
 // (four wavefronts, 128 rows, K ring of 2 and V ring of 3 tiles, copies one tile ahead), the
-// rest run the suffix body (four wavefront items, their private K tiles carved out of the same
-// LDS).  Workgroups start in index order; the prefix workgroups come first (or, when there are
+// rest run the suffix body (four wavefront items; it uses no LDS).  Workgroups start in index order; the prefix workgroups come first (or, when there are
 // more of them than CUs, evenly spread through the grid), so that a CU holds one prefix workgroup
 // and, beside it, suffix workgroups: each SIMD has one wavefront that multiplies and one that
 // streams, HBM is busy during the prefix pass, and there is no launch (with its ramp and tail)
@@ -25,7 +24,6 @@ namespace {
 
 constexpr int kFusedWaves = 4;
 constexpr int kFusedLds = prefix_impl::prefix_lds_bytes(2, 3);
-static_assert(kFusedWaves * suffix_impl::kWaveLdsBytes <= kFusedLds, "suffix tiles must fit");
 
 template <bool PAGED>
 __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_fused_kernel(
@@ -65,10 +63,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const long long item = sidx * kFusedWaves + wave;
-        typedef uint4 (*wave_tile_t)[suffix_impl::kRowU4];
-        suffix_impl::suffix_body<PAGED>(
-            p, p.suffix_slot0, item,
-            (wave_tile_t)((char*)lds + (size_t)wave * suffix_impl::kWaveLdsBytes));
+        suffix_impl::suffix_body<PAGED>(p, p.suffix_slot0, item);
     }
 }
 

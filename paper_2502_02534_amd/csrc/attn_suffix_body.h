@@ -5,16 +5,20 @@
 // share KV head j ride along as columns of one 16-wide MFMA tile, so the stream is
 // read once for all of them.  Per 32-token tile:
 //
-//   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = K rows (tokens) staged through LDS into
-//                 the operand layout, B = the G query rows (held in registers)
+//   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = K rows (tokens) loaded from global memory
+//                 straight into the operand layout (lane (c, r) takes 16 bytes of token
+//                 16 blk + c at byte 64 s + 16 r for step s: four lanes cover one 64-byte
+//                 stretch of a row), B = the G query rows (held in registers)
 //   online softmax in the base-2 domain on the accumulator registers; the accumulator
 //                 layout of S^T is exactly the A-operand layout of P, so P never moves
 //   O += P V      B = V transposed inside each lane with byte permutes (a lane loads the
 //                 same 16-byte column slice of 8 token rows and turns it into 8
 //                 token-contiguous fragments)
 //
-// Global loads are 16 bytes per lane with 16 adjacent lanes covering one 256-byte row.
-// The next tile's loads are issued before the current tile is computed.
+// Global loads are 16 bytes per lane; for V 16 adjacent lanes cover one 256-byte row.
+// The next tile's loads are issued before the current tile is computed, and with paged KV the
+// page numbers of the tile after that are fetched at the same time, so that no KV load waits
+// for a page-table load.  The body uses no LDS.
 // The running state is the deferred-division form of the paper's online-softmax
 // recurrence (App., attn task 2): (m, l, unnormalised accumulator).
 #pragma once
@@ -32,7 +36,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
 constexpr int kD = 128;
 constexpr int kTile = 32;        // tokens per tile
-constexpr int kRowU4 = 17;       // LDS row: 16 x 16 B of data + 16 B pad
 constexpr int kWavesPerBlock = 4;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v)
@@ -61,13 +64,9 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
     return *reinterpret_cast<const uint32_t*>(&r);
 }
 
-constexpr int kWaveLdsBytes = kTile * kRowU4 * 16;  // LDS of one wavefront
-
-// Body of one wavefront: work item `item`; `ksm` is the wavefront's own K tile in LDS
-// (kTile rows of kRowU4 uint4).  No workgroup barriers.
+// Body of one wavefront: work item `item`.  No LDS, no workgroup barriers.
 template <bool PAGED>
-__device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long long item,
-                                            uint4 (*ksm)[kRowU4])
+__device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long long item)
 {
 
     const int lane = threadIdx.x & 63;
@@ -94,13 +93,25 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
     const int last_page = PAGED ? (Ls - 1) / 16 : 0;
     constexpr int kRow = kD * 2 / 16;  // uint4 per KV row
 
-    // uint4 index of (token t of this sample, head j, 16-byte piece c)
-    auto row_index = [&](int t) -> long long {
+    // Page numbers of the two 16-token pages a tile covers (a tile starts on an even page).
+    struct TilePages {
+        long long a, b;
+    };
+    auto tile_pages = [&](int tb) -> TilePages {
+        TilePages tp = {0, 0};
         if (PAGED) {
-            const long long pg = pages[min(t >> 4, last_page)];
-            return ((pg * p.Hkv + j) * 16 + (t & 15)) * kRow + c;
+            tp.a = pages[min(tb >> 4, last_page)];
+            tp.b = pages[min((tb >> 4) + 1, last_page)];
         }
-        return (((long long)n * p.max_suffix_len + t) * p.Hkv + j) * kRow + c;
+        return tp;
+    };
+    // uint4 index of (token t of this sample, head j, 16-byte piece 0); t lies in the tile at tb
+    auto row_index = [&](int t, int tb, const TilePages& tp) -> long long {
+        if (PAGED) {
+            const long long pg = (t >> 4) == (tb >> 4) ? tp.a : tp.b;
+            return ((pg * p.Hkv + j) * 16 + (t & 15)) * kRow;
+        }
+        return (((long long)n * p.max_suffix_len + t) * p.Hkv + j) * kRow;
     };
 
     // Query fragments: B operand, column n = query head j*G + c (zero beyond G),
@@ -117,20 +128,21 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
         }
     }
 
+    // K: register 4 blk + s of lane (c, r) = token 16 blk + c, channels 32 s + 8 r .. + 7 (the A operand of
+    // step s for token block blk).  V: register s of lane (r, c) = token tile_token(r, s), 16-byte piece c.
+    // Tokens past the end of the chunk are clamped to its last one (their scores are masked).
     uint4 kreg[8], vreg[8];
-    auto load_tile = [&](int tb, uint4 (&kk)[8], uint4 (&vv)[8]) __attribute__((always_inline)) {
+    auto load_tile = [&](int tb, const TilePages& tp, uint4 (&kk)[8], uint4 (&vv)[8]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int t = min(tb + tile_token(r, s), t1 - 1);
-            const long long idx = row_index(t);
-            kk[s] = kg[idx];
-            vv[s] = vg[idx];
+        for (int blk = 0; blk < 2; ++blk) {
+            const long long kidx = row_index(min(tb + 16 * blk + c, t1 - 1), tb, tp);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                kk[4 * blk + s] = kg[kidx + 4 * s + r];
         }
-    };
-    auto stage_k = [&](const uint4 (&kk)[8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-            ksm[tile_token(r, s)][c] = kk[s];
+            vv[s] = vg[row_index(min(tb + tile_token(r, s), t1 - 1), tb, tp) + c];
     };
 
     float m_run = -INFINITY;  // running maximum of query head c (replicated over lane-rows)
@@ -140,8 +152,8 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
     for (int i = 0; i < 8; ++i)
         o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    load_tile(t0, kreg, vreg);
-    stage_k(kreg);
+    load_tile(t0, tile_pages(t0), kreg, vreg);
+    TilePages pages_next = tile_pages(min(t0 + kTile, t1 - 1) & ~(kTile - 1));
 
     for (int tb = t0; tb < t1; tb += kTile) {
         const bool more = tb + kTile < t1;
@@ -151,8 +163,10 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
             knext[s] = make_uint4(0, 0, 0, 0);
             vnext[s] = make_uint4(0, 0, 0, 0);
         }
-        if (more)
-            load_tile(tb + kTile, knext, vnext);
+        if (more) {
+            load_tile(tb + kTile, pages_next, knext, vnext);
+            pages_next = tile_pages(min(tb + 2 * kTile, t1 - 1) & ~(kTile - 1));
+        }
 
         // ---- S^T = K Q^T for the two 16-token blocks ---------------------------------------
         floatx4 sacc[2];
@@ -161,8 +175,7 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
             sacc[blk] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const bf16x8 kf = as_bf16x8(ksm[16 * blk + c][4 * s + r]);
-                sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], sacc[blk], 0, 0, 0);
+                sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[4 * blk + s]), qf[s], sacc[blk], 0, 0, 0);
             }
         }
         // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c;
@@ -223,10 +236,11 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
         }
 
         if (more) {
-            stage_k(knext);
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
+            for (int s = 0; s < 8; ++s) {
+                kreg[s] = knext[s];
                 vreg[s] = vnext[s];
+            }
         }
     }
 

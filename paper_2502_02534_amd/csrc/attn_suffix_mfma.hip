@@ -9,9 +9,8 @@ using namespace suffix_impl;
 template <bool PAGED>
 __global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int slot0)
 {
-    __shared__ uint4 ksm[kWavesPerBlock][kTile][kRowU4];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    suffix_body<PAGED>(p, slot0, (long long)blockIdx.x * kWavesPerBlock + wave, ksm[wave]);
+    suffix_body<PAGED>(p, slot0, (long long)blockIdx.x * kWavesPerBlock + wave);
 }
 
 }  // namespace
