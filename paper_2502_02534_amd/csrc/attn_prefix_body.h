@@ -296,7 +296,12 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, const PrefixLev
     // kAhead ahead of their MFMA.
     // Ring of fragment registers: kAhead + 1 reads in flight, and one more slot so that a new
     // read never targets the registers of the MFMA issued just before it.
+    // A K fragment is one 128-bit read into `ring`; a V fragment is two 64-bit reads into
+    // `ring_lo` / `ring_hi`, put together only after the wait that precedes its MFMA (the wait
+    // names all of them as operands, so nothing that reads a fragment register can be placed
+    // before the data has arrived).
     u32x4 ring[kAhead + 2];
+    u32x2 ring_lo[kAhead + 2], ring_hi[kAhead + 2];
     auto region = [&](auto qk_tag, auto pv_tag, int kstage, int vstage) __attribute__((always_inline)) {
         constexpr bool QK = decltype(qk_tag)::value, PV = decltype(pv_tag)::value;
         constexpr int NF = frag_count<QK, PV>();
@@ -313,29 +318,34 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, const PrefixLev
             constexpr int K = decltype(kc)::value;
             if constexpr (K < NF) {
                 using F = Frag<QK, PV, K>;
-                u32x4& dst = ring[K % (kAhead + 2)];
                 if constexpr (!F::is_pv) {
                     const unsigned addr = kbase + k_row[F::b] + ((32u * F::a) ^ k_xor[F::b]);
+                    u32x4& dst = ring[K % (kAhead + 2)];
                     asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(addr));
                 } else {
-                    u32x2 lo, hi;
+                    u32x2& lo = ring_lo[K % (kAhead + 2)];
+                    u32x2& hi = ring_hi[K % (kAhead + 2)];
                     const unsigned a0 = vbase + v_off[F::b][0], a1 = vbase + v_off[F::b][1];
                     asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%4\n\tds_read_b64_tr_b16 %1, %3 offset:%4"
                                  : "=&v"(lo), "=&v"(hi)
                                  : "v"(a0), "v"(a1), "n"(F::a * 4096));
-                    dst = u32x4{lo[0], lo[1], hi[0], hi[1]};
                 }
             }
         };
         auto consume = [&](auto kc) __attribute__((always_inline)) {
             constexpr int K = decltype(kc)::value;
             using F = Frag<QK, PV, K>;
-            u32x4& f = ring[K % (kAhead + 2)];
-            asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(ops_after<QK, PV, K>()));
-            if constexpr (!F::is_pv)
+            if constexpr (!F::is_pv) {
+                u32x4& f = ring[K % (kAhead + 2)];
+                asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(ops_after<QK, PV, K>()));
                 sacc[F::b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f), qf[F::a], sacc[F::b], 0, 0, 0);
-            else
+            } else {
+                u32x2& lo = ring_lo[K % (kAhead + 2)];
+                u32x2& hi = ring_hi[K % (kAhead + 2)];
+                asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(ops_after<QK, PV, K>()));
+                const u32x4 f = {lo[0], lo[1], hi[0], hi[1]};
                 o[F::b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f), pf[F::a], o[F::b], 0, 0, 0);
+            }
         };
         for_each_index(issue, std::make_integer_sequence<int, kAhead + 1>{});
         for_each_index(
