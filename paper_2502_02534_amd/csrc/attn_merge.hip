@@ -4,7 +4,7 @@
 //   lse = (m + log2 l) ln 2.
 // This is the rescaling step of the paper's online-softmax recurrence (App., attn
 // task 2: `ExpMaxDiff`, `WeightedSumSingle`, `WeightedSumDouble`, `Div`) applied to
-// blocks instead of single tokens.  Empty ranges are skipped, so the initial state
+// blocks instead of single tokens.  Empty ranges carry l = 0 and weight 0, so the initial state
 // (-inf, 0, 0) is the identity.
 #include "spd_internal.h"
 
@@ -49,7 +49,10 @@ template <> struct PartVec<true> {
     }
 };
 
-template <bool HALF>
+// BATCH: output parts a thread loads at a time (8 when the row has at most 8 slots, else 32).
+// PERLANE: (m, l) pairs a thread may have to take (kMaxSlots / tpr, rounded up).  Both only size
+// register arrays: the smaller the arrays, the more workgroups a CU holds.
+template <bool HALF, int BATCH, int PERLANE>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p, int tpr /* threads per row */)
 {
     typedef typename PartVec<HALF>::type vec_t;
@@ -63,60 +66,34 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
     const long long row = (long long)blockIdx.x * rows_per_block + r_in;
     const bool row_ok = row < total;
 
-    // valid partials of the row: the splits of every prefix level that lie inside the group's
-    // length, then the suffix chunks inside the sample's length; cum[l] counts those before level l
-    int cum[kMaxLevels + 1];
-    int ns = 0;
-#pragma unroll
-    for (int l = 0; l <= kMaxLevels; ++l)
-        cum[l] = 0;
-    if (row_ok) {
-        const int n = (int)(row / p.Hq);
-#pragma unroll
-        for (int l = 0; l < kMaxLevels; ++l) {
-            int c = 0;
-            if (l < p.num_levels && p.mlev[l].split_tokens > 0) {
-                const int b = prompt_of_sample(p.mlev[l].sample_indptr, p.mlev[l].B, n);
-                c = (p.mlev[l].lens[b] + p.mlev[l].split_tokens - 1) / p.mlev[l].split_tokens;
-            }
-            cum[l + 1] = cum[l] + c;
-        }
-        const int Ls = p.suffix_lens[n];
-        ns = p.suffix_chunk_tokens > 0 ? (Ls + p.suffix_chunk_tokens - 1) / p.suffix_chunk_tokens : 0;
-    }
-    const int np = cum[kMaxLevels];
-    const int cnt = np + ns;
+    // Every slot of the row holds an (m, l) pair: the pass that owns a slot stores l = 0 when its
+    // token range is empty (a prefix split past the group's length, a suffix chunk past the
+    // sample's), and leaves the slot's output part unwritten.  The row therefore needs no lengths
+    // here; a slot with l = 0 gets weight 0 and its output part, though loaded, is not used.
+    const int S = row_ok ? p.num_slots : 0;
     const bool ch_ok = row_ok && 4 * c < p.D;
     const elem_t* base = (const elem_t*)p.part_acc + part_index(p, row_ok ? row : 0, 0) * p.D + 4 * c;
-    auto slot_at = [&](int i) {
-        int slot = p.suffix_slot0 + (i - np);
-#pragma unroll
-        for (int l = kMaxLevels - 1; l >= 0; --l)
-            if (i < cum[l + 1])
-                slot = p.mlev[l].slot0 + (i - cum[l]);
-        return slot;
-    };
-    // The first batch of accumulator loads does not need the weights: it is issued together
+    // The first batch of output-part loads does not need the weights: it is issued together
     // with the (m, l) loads so that both round trips overlap.
-    constexpr int kBatch = 32;
+    constexpr int kBatch = BATCH;
     vec_t v[kBatch];
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
         v[u] = PartVec<HALF>::zero();
-        if (ch_ok && u < cnt)
-            v[u] = *reinterpret_cast<const vec_t*>(base + (long long)slot_at(u) * p.D);
+        if (ch_ok && u < S)
+            v[u] = *reinterpret_cast<const vec_t*>(base + (long long)u * p.D);
     }
     // Weights: the tpr threads of a row (a power of two <= 64, aligned inside a wavefront) each
-    // take every tpr-th partial; maximum and sum go round the group with shuffles.
-    constexpr int kPerLane = kMaxSlots / 8;
+    // take every tpr-th slot; maximum and sum go round the group with shuffles.
+    constexpr int kPerLane = PERLANE;
     float2 mine[kPerLane];
     float m = -INFINITY;
 #pragma unroll
     for (int k = 0; k < kPerLane; ++k) {
         const int i = c + k * tpr;
         mine[k] = make_float2(-INFINITY, 0.f);
-        if (i < cnt)
-            mine[k] = p.part_ml[part_index(p, row, slot_at(i))];
+        if (i < S)
+            mine[k] = p.part_ml[part_index(p, row, i)];
         if (mine[k].y > 0.f)
             m = fmaxf(m, mine[k].x);
     }
@@ -127,7 +104,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
     for (int k = 0; k < kPerLane; ++k) {
         const int i = c + k * tpr;
         const float w = mine[k].y > 0.f ? mine[k].y * __builtin_amdgcn_exp2f(mine[k].x - m) : 0.f;
-        if (i < cnt)
+        if (i < S)
             wgt[r_in][i] = w;
         l += w;
     }
@@ -137,23 +114,25 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(AttnParams p,
     if (!ch_ok)
         return;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i0 = 0; i0 < cnt; i0 += kBatch) {
+    for (int i0 = 0; i0 < S; i0 += kBatch) {
         if (i0 > 0) {
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 v[u] = PartVec<HALF>::zero();
-                if (i0 + u < cnt)
-                    v[u] = *reinterpret_cast<const vec_t*>(base + (long long)slot_at(i0 + u) * p.D);
+                if (i0 + u < S)
+                    v[u] = *reinterpret_cast<const vec_t*>(base + (long long)(i0 + u) * p.D);
             }
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            const float w = i0 + u < cnt ? wgt[r_in][i0 + u] : 0.f;
-            const float4 f = PartVec<HALF>::widen(v[u]);
-            acc.x = fmaf(f.x, w, acc.x);
-            acc.y = fmaf(f.y, w, acc.y);
-            acc.z = fmaf(f.z, w, acc.z);
-            acc.w = fmaf(f.w, w, acc.w);
+            const float w = i0 + u < S ? wgt[r_in][i0 + u] : 0.f;
+            if (w != 0.f) {
+                const float4 f = PartVec<HALF>::widen(v[u]);
+                acc.x = fmaf(f.x, w, acc.x);
+                acc.y = fmaf(f.y, w, acc.y);
+                acc.z = fmaf(f.z, w, acc.z);
+                acc.w = fmaf(f.w, w, acc.w);
+            }
         }
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -184,10 +163,22 @@ hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s)
     const int rows_per_block = kMergeThreads / use;
     const long long total = (long long)p.N * p.Hq;
     const dim3 grid((unsigned)((total + rows_per_block - 1) / rows_per_block));
-    if (p.part_half)
-        hipLaunchKernelGGL(attn_merge_kernel<true>, grid, dim3(kMergeThreads), 0, s, p, use);
-    else
-        hipLaunchKernelGGL(attn_merge_kernel<false>, grid, dim3(kMergeThreads), 0, s, p, use);
+    const bool few = p.num_slots <= 8, wide = use >= 32;
+    const dim3 block(kMergeThreads);
+#define SPD_MERGE(HALF, BATCH, PERLANE) \
+    hipLaunchKernelGGL((attn_merge_kernel<HALF, BATCH, PERLANE>), grid, block, 0, s, p, use)
+    if (p.part_half) {
+        if (few && wide) SPD_MERGE(true, 8, kMaxSlots / 32);
+        else if (wide) SPD_MERGE(true, 32, kMaxSlots / 32);
+        else if (few) SPD_MERGE(true, 8, kMaxSlots / 8);
+        else SPD_MERGE(true, 32, kMaxSlots / 8);
+    } else {
+        if (few && wide) SPD_MERGE(false, 8, kMaxSlots / 32);
+        else if (wide) SPD_MERGE(false, 32, kMaxSlots / 32);
+        else if (few) SPD_MERGE(false, 8, kMaxSlots / 8);
+        else SPD_MERGE(false, 32, kMaxSlots / 8);
+    }
+#undef SPD_MERGE
     return hipGetLastError();
 }
 

@@ -68,8 +68,12 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnParams p, int slot0,
         kbase = (const T*)p.k_suffix;
         vbase = (const T*)p.v_suffix;
     }
-    if (t0 >= t1)
-        return;  // empty range: the merge never reads this slot
+    if (t0 >= t1) {
+        // empty range: l = 0 tells the merge to leave the slot out (its output part stays unwritten)
+        if (lane == 0)
+            p.part_ml[part_index(p, row, slot0 + part)] = make_float2(-INFINITY, 0.f);
+        return;
+    }
 
     const T* q = (const T*)p.q + (long long)row * D;
     float m = -INFINITY, l = 0.f;

@@ -151,8 +151,16 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, const PrefixLev
     const int Lp = lv.lens[b];
     const int t0 = split * lv.split_tokens;
     const int t1 = min(Lp, t0 + lv.split_tokens);
-    if (row0 >= rows_b || t0 >= t1)
+    if (row0 >= rows_b)
         return;
+    if (t0 >= t1) {
+        // empty split: l = 0 tells the merge to leave the slot out (its output part stays unwritten)
+        const int rr = row0 + wave * 32 + col;
+        if (rr < rows_b && h == 0)
+            p.part_ml[part_index(p, (long long)(s0 + rr / p.G) * p.Hq + j * p.G + rr % p.G, lv.slot0 + split)] =
+                make_float2(-INFINITY, 0.f);
+        return;
+    }
 
     const char* __restrict__ kg = (const char*)lv.k;
     const char* __restrict__ vg = (const char*)lv.v;

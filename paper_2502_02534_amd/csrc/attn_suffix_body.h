@@ -83,9 +83,13 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
     const int Ls = p.suffix_lens[n];
     const int t0 = chunk * p.suffix_chunk_tokens;
     const int t1 = min(Ls, t0 + p.suffix_chunk_tokens);
-    if (t0 >= t1)
-        return;
     const int G = p.G;
+    if (t0 >= t1) {
+        // empty chunk: l = 0 tells the merge to leave the slot out (its output part stays unwritten)
+        if (r == 0 && c < G)
+            p.part_ml[part_index(p, (long long)n * p.Hq + (long long)j * G + c, slot0 + chunk)] = make_float2(-INFINITY, 0.f);
+        return;
+    }
 
     const uint4* __restrict__ kg = (const uint4*)p.k_suffix;
     const uint4* __restrict__ vg = (const uint4*)p.v_suffix;

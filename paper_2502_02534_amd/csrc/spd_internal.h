@@ -16,14 +16,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 // sum 2^(s - m) v / l.  Inside a kernel the state is the deferred-division form of the paper's
 // online-softmax recurrence (App., attn task 2); the division by l happens once, when the state
 // is stored, which lets the bf16 path keep the stored output in fp16 (11 significant bits, three
-// more than the bf16 result it is merged into) at half the traffic.  An empty range has l == 0.
-// What the merge needs to know about one level of shared prefixes: which group a sample belongs to,
-// the group's length, and where the level's splits sit among a row's partial-state slots.
-struct MergeLevel {
-    const int* sample_indptr;
-    const int* lens;
-    int B, split_tokens, slot0;
-};
+// more than the bf16 result it is merged into) at half the traffic.  An empty range has l == 0;
+// the pass that owns a slot always stores its (m, l), so the merge needs no sequence lengths.
 constexpr int kMaxLevels = 4;
 
 // One level of shared prefixes as the prefix pass sees it.
@@ -70,7 +64,6 @@ struct AttnParams {
     int prefix_slot0; // first slot of the prefix level the prefix fields describe
     int suffix_slot0; // first slot of the suffix chunks
     int num_levels;   // levels of shared prefixes (1 for the plain shared-prefix call)
-    MergeLevel mlev[kMaxLevels];
     void* part_acc;   // [N*Hq][slots][D] normalised partial outputs, fp16 if part_half else fp32;
                       // a row's partial states are contiguous for the merge
     int part_half;

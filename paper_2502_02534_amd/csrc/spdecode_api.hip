@@ -175,11 +175,6 @@ int run_attention(const spd_attn_desc* desc, const void* q, int num_levels, cons
     p.num_slots = lp.num_slots;
     p.suffix_slot0 = lp.num_slots - lp.num_suffix_chunks;
     p.num_levels = num_levels;
-    for (int l = 0; l < spd::kMaxLevels; ++l)
-        p.mlev[l] = spd::MergeLevel{nullptr, nullptr, 0, 0, 0};
-    for (int l = 0; l < num_levels; ++l)
-        p.mlev[l] = spd::MergeLevel{levels[l].sample_indptr, levels[l].lens, levels[l].num_groups,
-                                    lp.split_tokens[l], lp.slot0[l]};
     p.part_acc = workspace;
     p.part_half = desc->dtype == SPD_BF16 ? 1 : 0;
     p.part_ml = (float2*)((char*)workspace + lp.acc_bytes);
