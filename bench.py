@@ -76,9 +76,9 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="input copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=20)
-    ap.add_argument("--loop-steps", type=int, default=0,
+    ap.add_argument("--loop-steps", type=int, default=24,
                     help="decode steps of the append + attention + sampler loop timed eagerly and as a "
-                         "replayed graph (0 = skip; single-layer contiguous workloads only)")
+                         "replayed graph (0 = skip; single-layer workloads only)")
     ap.add_argument("--no-also", action="store_true",
                     help="skip the other configurations measured beside the main one (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -237,7 +237,7 @@ def main() -> int:
 
     # ---- loop of decode steps with KV append (device-side lengths), eager and as a replayed graph ----
     loop_info = None
-    if args.loop_steps > 0 and sp.layers == 1 and sp.page_size == 0:
+    if args.loop_steps > 2 and sp.layers == 1:
         L = args.loop_steps
         host = cx["layers_host"][0]
         import copy as _copy
@@ -289,8 +289,9 @@ def main() -> int:
         graph_us = (time.perf_counter() - t0) / (L - 2) * 1e6
         loop_info = {"steps": L, "us_per_step_eager": eager_us, "us_per_step_graph": graph_us,
                      "tokens_per_sec_graph": sp.num_samples * 1e6 / graph_us,
-                     "note": "append_suffix_kv + attention + sample_tokens per step, per-step inputs selected "
-                             "on the device, lengths on the device; graph = one captured step replayed"}
+                     "note": "decode_step_select + append_suffix_kv + attention + sample_tokens + decode_step_record "
+                             "per step: library launches only, step counter and lengths on the device; "
+                             "graph = one captured step replayed"}
         del lp, gl, graph, q_s, k_s, v_s, u_s
 
     if args.calibrate_copy:

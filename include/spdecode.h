@@ -294,6 +294,36 @@ SPD_API int append_suffix_kv(const spd_attn_desc *desc,
                      const int32_t *last_tokens, int32_t end_token, int32_t *finished,
                      void *stream);
 
+/*
+ * A loop of decode steps replayed from one captured step (the paper generates up to 1024 tokens
+ * per sample, App. "Experiment settings"; every step is append + attention + sampling on new
+ * queries, keys, values and uniforms).  The step counter lives on the device, as a pair
+ * step_state = {current, next} of int64 that starts as {0, 0}:
+ *
+ *   decode_step_select  copies row `current` of every src (a [num_steps, row_bytes] array) to dst
+ *                       (row_bytes bytes) and sets next = current + 1; rows past the last one
+ *                       repeat the last one
+ *   decode_step_record  copies every src (row_bytes bytes) into row next - 1 of dst (a
+ *                       [num_steps, row_bytes] array; nothing is written past its end) and sets
+ *                       current = next
+ *
+ * so a step is select, the step's calls, record.  `copies` is host memory read during the call,
+ * 1 <= count <= SPD_MAX_STEP_COPIES; src, dst and step_state are device pointers; row_bytes is a
+ * positive multiple of 4, src and dst are 4-byte aligned (16-byte aligned rows are moved in
+ * 16-byte pieces).  Source and destination ranges must not overlap.  Both calls are kernel
+ * launches only (no memset, no allocation), fit for graph capture.  Returns spd_status.
+ */
+typedef struct spd_row_copy {
+    const void *src;
+    void *dst;
+    int64_t row_bytes;
+} spd_row_copy;
+#define SPD_MAX_STEP_COPIES 8
+SPD_API int decode_step_select(int64_t *step_state, int64_t num_steps,
+                       int32_t count, const spd_row_copy *copies, void *stream);
+SPD_API int decode_step_record(int64_t *step_state, int64_t num_steps,
+                       int32_t count, const spd_row_copy *copies, void *stream);
+
 /* Short description of a status code (static storage). */
 SPD_API const char *spd_status_string(int status);
 

@@ -44,6 +44,10 @@ class PrefixLevel(ctypes.Structure):
                 ("max_samples_per_group", ctypes.c_int32), ("max_len", ctypes.c_int64)]
 
 
+class RowCopy(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("row_bytes", ctypes.c_int64)]
+
+
 def load() -> ctypes.CDLL:
     """Load the HIP library.  Raises if it has not been built."""
     global _lib
@@ -78,6 +82,9 @@ def load() -> ctypes.CDLL:
     lib.shared_prefix_decode_attn_levels.argtypes = [dp, vp, ctypes.c_int32, lp] + [vp] * 5 + [i64, vp, vp, vp, sz, vp]
     lib.append_suffix_kv.restype = ctypes.c_int
     lib.append_suffix_kv.argtypes = [dp] + [vp] * 7 + [i64, vp, ctypes.c_int32, vp, vp]
+    for fn in (lib.decode_step_select, lib.decode_step_record):
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, i64, ctypes.c_int32, ctypes.POINTER(RowCopy), vp]
     _lib = lib
     return lib
 
@@ -162,6 +169,26 @@ def append_suffix_kv(desc: AttnDesc, k_new, v_new, k_suffix, v_suffix, suffix_le
         int(end_token), _ptr(finished), _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "append_suffix_kv")
+
+
+def make_row_copies(pairs):
+    """ctypes array of RowCopy from (src tensor, dst tensor, bytes per row) triples."""
+    arr = (RowCopy * len(pairs))()
+    for i, (src, dst, row_bytes) in enumerate(pairs):
+        arr[i] = RowCopy(src.data_ptr(), dst.data_ptr(), int(row_bytes))
+    return arr
+
+
+def decode_step_select(step_state, num_steps: int, copies, stream=None) -> None:
+    rc = load().decode_step_select(_ptr(step_state), int(num_steps), len(copies), copies, _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "decode_step_select")
+
+
+def decode_step_record(step_state, num_steps: int, copies, stream=None) -> None:
+    rc = load().decode_step_record(_ptr(step_state), int(num_steps), len(copies), copies, _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "decode_step_record")
 
 
 def make_levels(levels):

@@ -72,6 +72,19 @@ struct AttnParams {
     float* lse;
 };
 
+// Row copies of one decode step (select: out of [steps, ...] tensors; record: into them).
+constexpr int kMaxStepCopies = 8;
+struct StepRowsParams {
+    long long* state;      // {current step, next step}
+    long long num_steps;
+    int count;
+    int first_block[kMaxStepCopies + 1];  // workgroups of copy i: first_block[i] .. first_block[i+1]-1
+    const void* src[kMaxStepCopies];
+    void* dst[kMaxStepCopies];
+    long long row_bytes[kMaxStepCopies];
+    int wide[kMaxStepCopies];  // 16-byte pieces (else 4-byte)
+};
+
 struct KvAppendParams {
     int N, Hkv, D, elt, page_size;
     int capacity;             // tokens a sample's slot (or page list) can hold
@@ -142,6 +155,8 @@ bool attn_fused_levels_supported(const AttnParams& p, const FusedLevels& fl);
 hipError_t launch_attn_fused_levels(const AttnParams& p, const FusedLevels& fl, hipStream_t s);
 hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
 hipError_t launch_kv_append(const KvAppendParams& a, hipStream_t s);
+long long step_rows_blocks(long long row_bytes);
+hipError_t launch_step_rows(const StepRowsParams& a, bool record, hipStream_t s);
 size_t sampler_workspace_bytes(long long rows, long long vocab);
 hipError_t launch_sampler(const SamplerParams& p, void* workspace, hipStream_t s);
 

@@ -84,6 +84,52 @@ int append_suffix_kv(const spd_attn_desc* desc, const void* k_new, const void* v
     return spd::launch_kv_append(a, (hipStream_t)stream) == hipSuccess ? SPD_OK : SPD_ELAUNCH;
 }
 
+static int step_rows(int64_t* step_state, int64_t num_steps, int32_t count, const spd_row_copy* copies,
+                     bool record, void* stream)
+{
+    static_assert(SPD_MAX_STEP_COPIES == spd::kMaxStepCopies, "header and kernel agree on the number of copies");
+    if (!step_state || misaligned(step_state, 8) || num_steps < 1 || count < 1 || count > SPD_MAX_STEP_COPIES || !copies)
+        return SPD_EINVAL;
+    spd::StepRowsParams a;
+    a.state = (long long*)step_state;
+    a.num_steps = num_steps;
+    a.count = count;
+    long long blocks = 0;
+    for (int i = 0; i < spd::kMaxStepCopies; ++i) {
+        a.first_block[i] = (int)blocks;
+        a.src[i] = nullptr;
+        a.dst[i] = nullptr;
+        a.row_bytes[i] = 0;
+        a.wide[i] = 0;
+        if (i >= count)
+            continue;
+        const spd_row_copy& c = copies[i];
+        if (!c.src || !c.dst || c.row_bytes <= 0 || c.row_bytes % 4 != 0 || misaligned(c.src, 4) || misaligned(c.dst, 4))
+            return SPD_EINVAL;
+        a.src[i] = c.src;
+        a.dst[i] = c.dst;
+        a.row_bytes[i] = c.row_bytes;
+        a.wide[i] = (c.row_bytes % 16 == 0 && !misaligned(c.src, 16) && !misaligned(c.dst, 16)) ? 1 : 0;
+        blocks += spd::step_rows_blocks(c.row_bytes);
+        if (blocks > 0x7fffffffLL)
+            return SPD_EUNSUPPORTED;
+    }
+    a.first_block[spd::kMaxStepCopies] = (int)blocks;
+    for (int i = count; i < spd::kMaxStepCopies; ++i)
+        a.first_block[i] = (int)blocks;
+    return spd::launch_step_rows(a, record, (hipStream_t)stream) == hipSuccess ? SPD_OK : SPD_ELAUNCH;
+}
+
+int decode_step_select(int64_t* step_state, int64_t num_steps, int32_t count, const spd_row_copy* copies, void* stream)
+{
+    return step_rows(step_state, num_steps, count, copies, false, stream);
+}
+
+int decode_step_record(int64_t* step_state, int64_t num_steps, int32_t count, const spd_row_copy* copies, void* stream)
+{
+    return step_rows(step_state, num_steps, count, copies, true, stream);
+}
+
 const char* spd_status_string(int status)
 {
     switch (status) {

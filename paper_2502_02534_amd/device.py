@@ -112,11 +112,12 @@ class DecodeLoop:
     """A loop of decode steps on the device: append the step's K/V (synthetic: there are no
     weights), attention, sampling; lengths, finished flags and the step counter live on the
     device, so the steps can be replayed from a captured graph without host synchronisation.
+    Every kernel of a step is one of the library's own launches.
 
-    Per-step inputs are rows of tensors indexed by a device-side step counter:
+    Per-step inputs are rows of tensors indexed by the device-side step counter:
       q_steps [steps, N, Hq, D], k_steps / v_steps [steps, N, Hkv, D], u_steps [steps, rows].
-    The logits are the same every step (only the uniforms change); `tokens_steps` and `out_steps`
-    record every step's results for checking."""
+    The logits are the same every step (only the uniforms change); `tokens_steps`, `out_steps`
+    and `lens_steps` record every step's results for checking."""
 
     def __init__(self, attn: DeviceAttn, sampler: DeviceSampler, q_steps, k_steps, v_steps, u_steps,
                  end_token: int = -1):
@@ -125,7 +126,7 @@ class DecodeLoop:
         self.steps = q_steps.shape[0]
         dev = q_steps.device
         n = attn.q.shape[0]
-        self.step = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.step = torch.zeros(2, dtype=torch.int64, device=dev)  # {current, next}
         self.finished = torch.zeros(n, dtype=torch.int32, device=dev)
         self.end_token = end_token
         sampler.tokens.fill_(-1)  # "no token yet": never equal to an end token (>= 0)
@@ -134,25 +135,24 @@ class DecodeLoop:
         self.tokens_steps = torch.full((self.steps, sampler.tokens.shape[0]), -1, dtype=torch.int32, device=dev)
         self.out_steps = torch.zeros((self.steps,) + tuple(attn.out.shape), dtype=attn.out.dtype, device=dev)
         self.lens_steps = torch.zeros((self.steps, n), dtype=torch.int32, device=dev)
+        nbytes = lambda t: t.numel() * t.element_size()
+        self._select = B.make_row_copies([(q_steps, attn.q, nbytes(attn.q)), (k_steps, self.k_cur, nbytes(self.k_cur)),
+                                          (v_steps, self.v_cur, nbytes(self.v_cur)),
+                                          (u_steps, sampler.uniforms, nbytes(sampler.uniforms))])
+        self._record = B.make_row_copies([(sampler.tokens, self.tokens_steps, nbytes(sampler.tokens)),
+                                          (attn.out, self.out_steps, nbytes(attn.out)),
+                                          (attn.suffix_lens, self.lens_steps, nbytes(attn.suffix_lens))])
 
     def one_step(self) -> None:
-        """Enqueues one decode step on the current stream (capturable: no allocation that the
-        caching allocator cannot replay, no synchronisation)."""
+        """Enqueues one decode step on the current stream (capturable: kernel launches only)."""
         a, s = self.attn, self.sampler
-        idx = self.step  # device-side counter
-        a.q.copy_(self.q_steps.index_select(0, idx)[0])
-        self.k_cur.copy_(self.k_steps.index_select(0, idx)[0])
-        self.v_cur.copy_(self.v_steps.index_select(0, idx)[0])
-        s.uniforms.copy_(self.u_steps.index_select(0, idx)[0])
+        B.decode_step_select(self.step, self.steps, self._select)
         B.append_suffix_kv(a.desc, self.k_cur, self.v_cur, a.k_suffix, a.v_suffix, a.suffix_lens,
                            a.suffix_page_indptr, a.suffix_page_indices, a.max_suffix_len,
                            s.tokens, self.end_token, self.finished)
         a.run()
         s.run()
-        self.tokens_steps.index_copy_(0, idx, s.tokens.unsqueeze(0))
-        self.out_steps.index_copy_(0, idx, a.out.unsqueeze(0))
-        self.lens_steps.index_copy_(0, idx, a.suffix_lens.unsqueeze(0))
-        self.step.add_(1)
+        B.decode_step_record(self.step, self.steps, self._record)
 
 
 @dataclasses.dataclass

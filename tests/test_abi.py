@@ -140,3 +140,20 @@ def test_levels_and_append_entry_points_check_their_arguments(lib):
     paged = B.make_desc(dtype=B.SPD_BF16, num_q_heads=32, num_kv_heads=8, head_dim=128, num_prompts=1,
                         num_samples=64, page_size=16)
     assert lib.append_suffix_kv(ctypes.byref(paged), o, o, o, o, o, z, z, 512, z, -1, z, z) == 1
+
+
+def test_step_calls_check_their_arguments(lib):
+    from paper_2502_02534_amd import binding as B
+    z = ctypes.c_void_p(0)
+    st = ctypes.c_void_p(256)   # never dereferenced: the checks below fail first
+    ok = (B.RowCopy * 1)(B.RowCopy(256, 512, 64))
+    for fn in (lib.decode_step_select, lib.decode_step_record):
+        assert fn(z, 4, 1, ok, z) == 1                          # no step counter
+        assert fn(ctypes.c_void_p(260), 4, 1, ok, z) == 1       # counter not 8-byte aligned
+        assert fn(st, 0, 1, ok, z) == 1                         # no steps
+        assert fn(st, 4, 0, ok, z) == 1                         # no copies
+        assert fn(st, 4, 9, ok, z) == 1                         # more copies than SPD_MAX_STEP_COPIES
+        assert fn(st, 4, 1, None, z) == 1
+        for bad in (B.RowCopy(0, 512, 64), B.RowCopy(256, 0, 64), B.RowCopy(256, 512, 0),
+                    B.RowCopy(256, 512, 6), B.RowCopy(258, 512, 64), B.RowCopy(256, 514, 64)):
+            assert fn(st, 4, 1, (B.RowCopy * 1)(bad), z) == 1

@@ -150,3 +150,31 @@ def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i):
     assert torch.equal(g_loop.lens_steps, loop.lens_steps)
     assert torch.equal(g_loop.tokens_steps, loop.tokens_steps)
     assert torch.equal(g_loop.out_steps.view(torch.uint8), loop.out_steps.view(torch.uint8))
+
+
+def test_step_select_and_record_follow_the_device_counter(dev):
+    """Rows chosen by the device-side counter: wide (16-byte) and narrow (4-byte) copies, rows
+    longer than one workgroup's share, the last row repeated by select past the end, nothing
+    recorded past the end, and the counter pair after every call."""
+    from paper_2502_02534_amd import binding as B
+    steps = 5
+    g = torch.Generator(device="cpu").manual_seed(3)
+    big = torch.randint(-2**31, 2**31 - 1, (steps, 40000), dtype=torch.int32, generator=g).cuda()   # 160000 B rows
+    odd = torch.randint(-2**31, 2**31 - 1, (steps, 7), dtype=torch.int32, generator=g).cuda()       # 28 B rows
+    shifted = torch.randint(-2**31, 2**31 - 1, (steps * 12 + 1,), dtype=torch.int32, generator=g).cuda()[1:].view(steps, 12)
+    big_now, odd_now, sh_now = torch.zeros(40000, dtype=torch.int32).cuda(), torch.zeros(7, dtype=torch.int32).cuda(), \
+        torch.zeros(12, dtype=torch.int32).cuda()
+    rec_big, rec_odd = torch.full_like(big, -1), torch.full_like(odd, -1)
+    state = torch.zeros(2, dtype=torch.int64).cuda()
+    sel = B.make_row_copies([(big, big_now, 160000), (odd, odd_now, 28), (shifted, sh_now, 48)])
+    rec = B.make_row_copies([(big_now, rec_big, 160000), (odd_now, rec_odd, 28)])
+    for t in range(steps + 2):
+        B.decode_step_select(state, steps, sel)
+        torch.cuda.synchronize()
+        row = min(t, steps - 1)
+        assert state.tolist() == [t, t + 1]
+        assert torch.equal(big_now, big[row]) and torch.equal(odd_now, odd[row]) and torch.equal(sh_now, shifted[row])
+        B.decode_step_record(state, steps, rec)
+        torch.cuda.synchronize()
+        assert state.tolist() == [t + 1, t + 1]
+    assert torch.equal(rec_big, big) and torch.equal(rec_odd, odd)
