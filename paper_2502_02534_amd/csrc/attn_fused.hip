@@ -47,19 +47,16 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
         sidx = (long long)blockIdx.x - prefix_blocks;
     }
     if (pidx >= 0) {
-        // the prefix level this workgroup belongs to; within a level: split fastest, then row tile,
-        // then (group, KV head)
+        // the prefix level this workgroup belongs to
         int l = 0;
 #pragma unroll
         for (int k = 1; k < kMaxLevels; ++k)
             if (k < fl.num_levels && pidx >= fl.first_block[k])
                 l = k;
         const PrefixLevelParams& lv = fl.level[l];
-        const int local = pidx - fl.first_block[l];
-        const int split = local % lv.num_splits;
-        const int rest = local / lv.num_splits;
-        prefix_impl::prefix_body<kFusedWaves, PAGED, 2, 3, 1>(p, lv, lds, split, rest % lv.rowtiles,
-                                                              rest / lv.rowtiles);
+        const prefix_impl::PrefixItem it =
+            prefix_impl::prefix_item(pidx - fl.first_block[l], lv.num_splits, lv.rowtiles, lv.groups * p.Hkv);
+        prefix_impl::prefix_body<kFusedWaves, PAGED, 2, 3, 1>(p, lv, lds, it.split, it.rowtile, it.z);
     } else {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const long long item = sidx * kFusedWaves + wave;

@@ -122,6 +122,35 @@ __host__ __device__ inline PrefixLevelParams level_of(const AttnParams& p, int r
     return lv;
 }
 
+// Which (split, row tile, z = group * Hkv + KV head) the prefix workgroup with index `local` of a
+// level takes.  Workgroups go to the eight XCDs in turn (index mod 8), and every XCD has an L2 of
+// its own: the row tiles of one (split, z) read the same K and V, so they are given indices that
+// agree mod 8 and follow one another, which puts them on one XCD at the same time (the prompt is
+// then fetched into one L2 once instead of into as many L2s as there are row tiles).  That
+// takes a number of (split, z) units divisible by 8; otherwise the split runs fastest, then the
+// row tile, then z.
+struct PrefixItem {
+    int split, rowtile, z;
+};
+__device__ __forceinline__ PrefixItem prefix_item(int local, int num_splits, int rowtiles, int zs)
+{
+    PrefixItem it;
+    const int units = num_splits * zs;
+    if (rowtiles > 1 && (units & 7) == 0) {
+        const int slot = local >> 3;
+        const int u = (local & 7) + 8 * (slot / rowtiles);
+        it.rowtile = slot % rowtiles;
+        it.split = u % num_splits;
+        it.z = u / num_splits;
+    } else {
+        it.split = local % num_splits;
+        const int rest = local / num_splits;
+        it.rowtile = rest % rowtiles;
+        it.z = rest / rowtiles;
+    }
+    return it;
+}
+
 // LDS of a workgroup: KS slots for K tiles followed by VS slots for V tiles.
 constexpr int prefix_lds_bytes(int KS, int VS) { return (KS + VS) * kTileBytes; }
 

@@ -10,11 +10,12 @@ using namespace prefix_impl;
 // 256-row workgroups (8 wavefronts) keep the long rings, copies two tiles ahead.
 template <int WAVES, bool PAGED>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES == 4 ? 2 : 1, 2))) void
-attn_prefix_mfma_kernel(AttnParams p)
+attn_prefix_mfma_kernel(AttnParams p, int rowtiles)
 {
     constexpr int KS = WAVES == 4 ? 2 : 4, VS = WAVES == 4 ? 3 : 4, AHEAD = WAVES == 4 ? 1 : 2;
     __shared__ uint4 lds[prefix_lds_bytes(KS, VS) / 16];
-    prefix_body<WAVES, PAGED, KS, VS, AHEAD>(p, level_of(p, (int)gridDim.y), lds, blockIdx.x, blockIdx.y, blockIdx.z);
+    const PrefixItem it = prefix_item((int)blockIdx.x, p.num_prefix_splits, rowtiles, p.B * p.Hkv);
+    prefix_body<WAVES, PAGED, KS, VS, AHEAD>(p, level_of(p, rowtiles), lds, it.split, it.rowtile, it.z);
 }
 
 template <int WAVES>
@@ -22,11 +23,14 @@ hipError_t launch_waves(const AttnParams& p, hipStream_t s)
 {
     constexpr int kBlockRows = 32 * WAVES;
     const int rowtiles = (p.max_spp * p.G + kBlockRows - 1) / kBlockRows;
-    const dim3 grid(p.num_prefix_splits, rowtiles, p.B * p.Hkv);
+    const long long blocks = (long long)p.num_prefix_splits * rowtiles * p.B * p.Hkv;
+    if (blocks > 0x7fffffffLL)
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks);
     if (p.page_size)
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, true>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, true>), grid, dim3(WAVES * 64), 0, s, p, rowtiles);
     else
-        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, false>), grid, dim3(WAVES * 64), 0, s, p);
+        hipLaunchKernelGGL((attn_prefix_mfma_kernel<WAVES, false>), grid, dim3(WAVES * 64), 0, s, p, rowtiles);
     return hipGetLastError();
 }
 
