@@ -779,18 +779,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
         if (tail[k] != -INFINITY)
             bin_one(tail[k]);
     lds_barrier();  // histogram complete
-    if (wave == 0) {
-        unsigned far_units = L.hist[kPubBins + lane];
-        for (int o = 32; o > 0; o >>= 1)
-            far_units += __shfl_xor(far_units, o);
-        if (lane == 0)
-            L.hist[kPubBins - 1] += far_units;
-    }
-    lds_barrier();
+    // what the lanes collected past the last bin belongs to the last bin (every wavefront adds the
+    // places up for itself; only the owner of the last bin uses the sum)
+    static_assert(kPubBins == 2 * kBlock, "thread t owns bins 2t and 2t+1; the last thread owns the last bin");
+    unsigned far_units = L.hist[kPubBins + lane];
+    for (int o = 32; o > 0; o >>= 1)
+        far_units += __shfl_xor(far_units, o);
 
     // ---- running sums over the bins (thread t owns bins 2t, 2t+1): fixed-point units for the element
     // counts, estimated mass for the slice's own cut bin ----
-    const unsigned q0 = L.hist[2 * tid], q1 = L.hist[2 * tid + 1];
+    const unsigned q0 = L.hist[2 * tid], q1 = L.hist[2 * tid + 1] + (tid == kBlock - 1 ? far_units : 0u);
     const double m0 = (double)q0 * bin_unit(2 * tid), m1 = (double)q1 * bin_unit(2 * tid + 1);
     unsigned qi = q0 + q1;
     double mi = m0 + m1;
@@ -931,17 +929,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
                 out[base + i] = L.stage[wave][i];
     *reinterpret_cast<uint2*>(&W.hist[(size_t)slice * kPubBins + 2 * tid]) = make_uint2(q0, q1);
     // ---- segment sums: what lies above the window (nothing when the window starts at the top) ----
-    float s_seg[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-        s_seg[j] = 0.f;
+    float a1 = 0.f;
     if (win_hi >= 0 && win_lo > 0) {
+        float s_seg[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            s_seg[j] = 0.f;
 #pragma unroll
         for (int q = 0; q < 32; ++q)
             if (xv[q] * rc.c16 >= t_above)
                 s_seg[q >> 2] += prob(xv[q], rs);
+        a1 = fold_segments(s_seg);
     }
-    const float a1 = fold_segments(s_seg);
     if ((lane & 7) == 0)
         seg_out[(lane >> 3) * kWaves + wave] = (double)a1;
 }
