@@ -250,8 +250,12 @@ SPD_API int sample_tokens_static(const void *logits, int32_t logits_dtype,
  *
  *   top_k   int32 [rows] or NULL (= off everywhere); 0 = off for the row
  *   min_p   float [rows] or NULL; 0 = off for the row; values in (0, 1]
- * With both NULL this is sample_tokens.  Rows with a filter take a one-workgroup-per-row kernel
- * that reads the row several times; it is exact, not fast.  Everything else as for sample_tokens.
+ * With both NULL this is sample_tokens.  Rows with a filter run through the same kernels as
+ * sample_tokens when what the filters keep lies within the few thousand most probable tokens of
+ * each 16384-token stretch of the row (top-k up to about a thousand, min-p down to about 1e-3 on
+ * ordinary logits); otherwise, and for rows that are not 16-byte aligned, they take a
+ * one-workgroup-per-row routine that reads the row several times (exact, about ten times slower).
+ * Everything else as for sample_tokens.
  */
 SPD_API int sample_tokens_filtered(const void *logits, int32_t logits_dtype,
                            int64_t rows, int64_t vocab, int64_t row_stride,

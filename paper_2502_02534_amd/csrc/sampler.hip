@@ -660,7 +660,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
     const float T = sp.temperature[r];
     const bool greedy = (T == 0.f);
     const float top_p = sp.top_p[r];
-    const bool cut = !greedy && top_p < 1.f;
+    // rows with a min-p or top-k filter are finished from their pairs alone, whatever top_p is
+    const bool filtered = (sp.top_k && sp.top_k[r] > 0) || (sp.min_p && sp.min_p[r] > 0.f);
+    const bool cut = !greedy && (top_p < 1.f || filtered);
 
     float xv[32];
     SPD_LOAD_SLICE(xv, x, g, tid)
@@ -834,11 +836,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
     const int Lb = L.cut_bin;
     auto units = [&](int a, int z) { return L.cumq[z] - (a > 0 ? L.cumq[a - 1] : 0u); };
     auto fits = [&](int a, int z) { return (int)(units(a, z) >> 15) <= cap; };
-    const bool from_top = fits(0, min(Lb + kTopProbe, kPubBins - 1));
+    // (a row with a filter: always from the top, as many bins as fit; its filters decide later how
+    // far down they reach)
+    const bool from_top = filtered || fits(0, min(Lb + kTopProbe, kPubBins - 1));
     int mine = -1;
     if (from_top) {
         // bins 0 .. z, z as large as fits, at most L + kTopMargin
-        const int zmax = min(Lb + kTopMargin, kPubBins - 1);
+        const int zmax = filtered ? kPubBins - 1 : min(Lb + kTopMargin, kPubBins - 1);
         if (2 * tid + 1 <= zmax && (int)(qi >> 15) <= cap)
             mine = 2 * tid + 1;
         else if (2 * tid <= zmax && (int)((qi - q1) >> 15) <= cap)
@@ -1041,6 +1045,9 @@ struct FinishLds {
     uint32_t kmin[kWaves], kmax[kWaves];
 };
 
+// FILTERED = false takes the rows without a min-p / top-k filter, FILTERED = true the rows with one
+// (a launch with filter arrays runs both; each leaves the other's rows alone).
+template <bool FILTERED>
 __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
 {
     __shared__ FinishLds L;
@@ -1052,6 +1059,10 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     const float T = sp.temperature[r];
     const float top_p = sp.top_p[r];
     const bool greedy = (T == 0.f);
+    const int top_k = sp.top_k ? sp.top_k[r] : 0;
+    const float min_p = sp.min_p ? sp.min_p[r] : 0.f;
+    if (((top_k > 0 || min_p > 0.f) && !greedy) != FILTERED)
+        return;
     const bool cut = !greedy && top_p < 1.f;
     const int nseg = slices * kSegPerSlice;
     double* seg_mass = L.row.seg_mass;
@@ -1100,13 +1111,12 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     __syncthreads();
 
     int lo = kBins, hi = kBins;  // candidate bins, counted down from the maximum's bin; kBins = no cut
-    if (cut) {
-        // Estimate of the nucleus cut from the slices' histograms.  Bin b of slice s is bin
-        // b + shift[s] of the row; thread t gathers row bins 4 t .. 4 t + 3 (all loads of eight
-        // slices are requested before any is used; loads are unconditional from clamped
-        // positions, what lies outside a slice's bins is masked afterwards).
-        const int rb0 = kBinsPerThread * tid;
-        unsigned long long qsum[kBinsPerThread];
+    // Units of the slices' histograms per row bin: bin b of slice s is bin b + shift[s] of the row;
+    // thread t gathers row bins 4 t .. 4 t + 3 (all loads of eight slices are requested before any
+    // is used; loads are unconditional from clamped positions, what lies outside a slice's bins is
+    // masked afterwards).
+    const int rb0 = kBinsPerThread * tid;
+    auto gather_units = [&](unsigned long long (&qsum)[kBinsPerThread]) __attribute__((always_inline)) {
 #pragma unroll
         for (int k = 0; k < kBinsPerThread; ++k)
             qsum[k] = 0ull;
@@ -1131,6 +1141,11 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
                     qsum[k] += (b >= 0 && b < kPubBins) ? qv[u][k] : 0u;
                 }
         }
+    };
+    if (cut && !FILTERED) {
+        // Estimate of the nucleus cut from the slices' histograms.
+        unsigned long long qsum[kBinsPerThread];
+        gather_units(qsum);
 #pragma unroll
         for (int k = 0; k < kBinsPerThread; ++k)
             L.row.hist[rank_slot(rb0 + k)] = (double)qsum[k] * bin_unit(rb0 + k);
@@ -1148,8 +1163,8 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     // A slice is covered when its emitted bins contain the row's cut bins and everything it summed
     // as above its window is above `lo` (bin b of the slice is bin b + shift of the row).
     if (tid < slices) {
-        bool ok = true;
-        if (cut) {
+        bool ok = !FILTERED;  // (a row with a filter is finished from its pairs further down)
+        if (cut && !FILTERED) {
             const int a = L.swin_lo[tid], z = L.swin_hi[tid], sh = L.shift[tid];
             ok = L.scount[tid] >= 0 && z >= 0 && (a == 0 || a + sh <= lo) && (z >= kPubBins - 1 || hi <= z + sh);
         }
@@ -1202,10 +1217,84 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
             }
         }
     };
+    // One wavefront-wide append to the candidate list.
+    auto append = [&](bool want, unsigned long long pair) __attribute__((always_inline)) {
+        const unsigned long long mask = __ballot(want);
+        if (mask != 0ull) {
+            unsigned base = 0u;
+            if (lane == 0)
+                base = atomicAdd(&L.cand_total, (unsigned)__popcll(mask));
+            base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+            if (want) {
+                const unsigned pos = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+                if (pos < (unsigned)kCandCap)
+                    L.cand[pos] = pair;
+            }
+        }
+    };
+    // Radix select over the order keys of the first C candidates, taken relative to the largest one
+    // (rel = kmax - key, 0 = most probable) so that only the bits in which the candidates differ
+    // are resolved: 11 bits per level, usually two levels.  Returns the key of the highest candidate
+    // whose upper set (on top of `above0`) reaches `need`, counting candidates (`by_count`) or
+    // summing their probabilities; `reached` is what that upper set amounts to, `bad` says that
+    // the candidates do not reach `need` at all.
+    auto radix_select = [&](int C, bool by_count, double above0, double need, bool& bad, double& reached) -> uint32_t {
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        for (int i = tid; i < C; i += kBlock) {
+            const uint32_t key = order_key(__uint_as_float((unsigned)L.cand[i]));
+            kmin = min(kmin, key);
+            kmax = max(kmax, key);
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+        }
+        __syncthreads();  // an earlier call's readers of kmin / kmax are through
+        if (lane == 0) {
+            L.kmin[wave] = kmin;
+            L.kmax[wave] = kmax;
+        }
+        double* H = L.row.hist;
+        for (int b = tid; b < kBins; b += kBlock)
+            H[b] = 0.0;
+        __syncthreads();
+        for (int w = 0; w < kWaves; ++w) {
+            kmin = min(kmin, L.kmin[w]);
+            kmax = max(kmax, L.kmax[w]);
+        }
+        const uint32_t span = C > 0 ? kmax - kmin : 0u;
+        const int nbits = span ? 32 - __clz((int)span) : 1;
+        uint32_t prefix = 0u;
+        double abv = above0;
+        bad = !(above0 < need);
+        for (int shift = 11 * ((nbits - 1) / 11); shift >= 0 && !bad; shift -= 11) {
+            for (int i = tid; i < C; i += kBlock) {
+                const float xc = __uint_as_float((unsigned)L.cand[i]);
+                const uint32_t rel = kmax - order_key(xc);
+                if ((uint64_t)rel >> (shift + 11) == prefix)
+                    atomicAdd(&H[rank_slot((rel >> shift) & 0x7ffu)], by_count ? 1.0 : (double)prob(xc, rs));
+            }
+            __syncthreads();
+            const BinPick pk = wave_pick(H, abv, need, false);
+            // the threshold must fall among the candidates
+            if (shift == 11 * ((nbits - 1) / 11) && !(above0 + pk.total >= need))
+                bad = true;
+            prefix = (prefix << 11) | (uint32_t)pk.bin;
+            abv = pk.above;
+            reached = pk.above + pk.in_bin;
+            __syncthreads();
+            if (shift > 0) {
+                for (int b = tid; b < kBins; b += kBlock)
+                    H[b] = 0.0;
+                __syncthreads();
+            }
+        }
+        return kmax - prefix;
+    };
     // pairs written out by the covered slices: four per thread and slice, all requested before any is
     // used (unconditional loads from clamped positions; what lies past a slice's count is masked)
     static_assert(kEmitCap == 4 * kBlock, "four pairs per thread and slice");
-    for (int s0 = 0; s0 < slices; s0 += 8) {
+    for (int s0 = 0; s0 < (FILTERED ? 0 : slices); s0 += 8) {
         unsigned long long ev[8][4];
         int cnt[8];
 #pragma unroll
@@ -1227,7 +1316,7 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
         f_part = 0.f;
     }
     // slices that are not covered: a second look at their logits
-    for (int s = 0; s < slices; ++s) {
+    for (int s = 0; s < (FILTERED ? 0 : slices); ++s) {
         if (L.covered[s])
             continue;
         const SliceRange g = slice_range(s, slice_elems, V);
@@ -1243,6 +1332,118 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
         s_part += (double)f_part;
         f_part = 0.f;
     }
+    uint32_t key_floor = 0u;  // rows with a filter: the lowest key that survives the filters
+    if (FILTERED) {
+        // ---- min-p and top-k ahead of the nucleus.  Both keep an upper set of the logits, and the scan
+        // kernel wrote such a row's slices out from the top, so everything that survives is among the
+        // pairs, provided every slice's window reaches as far down as the filters do; otherwise the
+        // row goes to the whole-row routine.  Survivors become the candidate list. ----
+        bool ok = slices <= 8;  // the pairs of a row stay in registers (four per thread and slice)
+        // top-k: the k-th largest logit lies in row bins b1 .. b2, by the element-count bounds of the
+        // histogram units (an element adds 32768 to 34219 units): the running units reach 32768 k no
+        // later than the k-th element's bin and 34219 k no earlier
+        int b1 = 0, b2 = 0;
+        if (top_k > 0) {
+            unsigned long long qsum[kBinsPerThread];
+            gather_units(qsum);
+#pragma unroll
+            for (int k = 0; k < kBinsPerThread; ++k)
+                L.row.hist[rank_slot(rb0 + k)] = (double)qsum[k];
+            __syncthreads();
+            const BinPick p1 = wave_pick(L.row.hist, 0.0, 32768.0 * (double)top_k, false);
+            const BinPick p2 = wave_pick(L.row.hist, 0.0, 34219.0 * (double)top_k, false);
+            b1 = p1.bin;
+            b2 = p2.bin;
+            // fewer than k elements inside the histogram's range: not a case for this path
+            ok = ok && p2.total >= 34219.0 * (double)top_k && b2 < kBins - 1;
+            __syncthreads();
+        }
+        // row bin that every slice's window has to reach: the k-th element's, else the last one that
+        // can hold p >= min_p (bins are 1/16 octave; two bins of slack for the rounding of p)
+        const int reach = top_k > 0 ? b2 : min(kBins - 1, (int)(-__log2f(min_p) * 16.f) + 2);
+        if (tid < slices) {
+            const int z = L.swin_hi[tid], sh = L.shift[tid];
+            L.covered[tid] = sh >= kBins ||
+                             (L.scount[tid] >= 0 && z >= 0 && L.swin_lo[tid] == 0 && (z >= kPubBins - 1 || z + sh >= reach));
+        }
+        __syncthreads();
+        for (int s = 0; s < slices; ++s)
+            ok = ok && L.covered[s];
+        if (!ok) {
+            sample_row_from_memory(sp, r, L.row);
+            return;
+        }
+        unsigned long long ev[8][4];
+        int cnt[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = min(u, slices - 1);
+            cnt[u] = (u < slices && L.shift[s] < kBins) ? min(L.scount[s], kEmitCap) : 0;
+            const unsigned long long* e = W.emit + (size_t)s * kEmitCap;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                ev[u][k] = e[tid + k * kBlock];
+        }
+        uint32_t key_k = 0u;
+        if (top_k > 0) {
+            // elements above bin b1 are counted, those in b1 .. b2 listed; the k-th largest is found
+            // among the listed ones by rank
+            const float t_b1 = b1 <= 0 ? INFINITY : kf_row - (float)b1 + 1.f;
+            const float t_b2 = kf_row - (float)b2;
+            int n_above = 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const bool live = tid + k * kBlock < cnt[u];
+                    const float t = __uint_as_float((unsigned)ev[u][k]) * rc.c16;
+                    const bool above = live && t >= t_b1;
+                    n_above += above ? 1 : 0;
+                    append(live && !above && t >= t_b2, ev[u][k]);
+                }
+            double da = (double)n_above, db = 0.0;
+            block_sum2_f64(da, db, L.row.scratch);  // (its barriers also complete the list)
+            const unsigned listed = L.cand_total;
+            const double rank = (double)top_k - da;
+            bool bad = listed > (unsigned)kCandCap || rank < 1.0;
+            double reached = 0.0;
+            if (!bad)
+                key_k = radix_select((int)listed, true, 0.0, rank, bad, reached);
+            if (bad) {
+                sample_row_from_memory(sp, r, L.row);
+                return;
+            }
+            __syncthreads();
+            if (tid == 0)
+                L.cand_total = 0u;
+            __syncthreads();
+        }
+        // survivors: at least as large as the k-th largest logit, and p >= min_p
+        uint32_t kfl = 0xffffffffu;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float xq = __uint_as_float((unsigned)ev[u][k]);
+                const uint32_t key = order_key(xq);
+                const float pq = prob(xq, rs);
+                const bool keep = tid + k * kBlock < cnt[u] && key >= key_k && pq >= min_p;
+                f_part += keep ? pq : 0.f;
+                kfl = keep ? min(kfl, key) : kfl;
+                append(keep, ev[u][k]);
+            }
+        s_part += (double)f_part;
+        for (int o = 32; o > 0; o >>= 1)
+            kfl = min(kfl, (uint32_t)__shfl_xor((int)kfl, o));
+        if (lane == 0)
+            L.kmin[wave] = kfl;
+        __syncthreads();
+        key_floor = 0xffffffffu;
+        for (int w = 0; w < kWaves; ++w)
+            key_floor = min(key_floor, L.kmin[w]);
+        lo = 0;            // no bin is kept wholesale,
+        hi = kBins - 1;    // every element is compared with the threshold
+    }
     __syncthreads();
     const unsigned cand_total = L.cand_total;
     const int C = (int)min(cand_total, (unsigned)kCandCap);
@@ -1250,69 +1451,19 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
     for (int sidx = tid; sidx < nseg; sidx += kBlock)
         above_total += seg_mass[sidx];
     block_sum2_f64(above_total, s_part, L.row.scratch);
-    const double need = (double)top_p * s_part;  // s_part: the row mass S
+    const double need = (double)top_p * s_part;  // s_part: the row mass S (of what the filters left)
 
-    uint32_t key_tau = 0u;
-    double Z = above_total;
-    if (cut) {
-        // Radix select over the candidates' order keys, taken relative to the largest one
-        // (rel = kmax - key, 0 = most probable) so that only the bits in which the candidates
-        // differ are resolved: 11 bits per level, usually two levels.
-        uint32_t kmin = 0xffffffffu, kmax = 0u;
-        for (int i = tid; i < C; i += kBlock) {
-            const uint32_t key = order_key(__uint_as_float((unsigned)L.cand[i]));
-            kmin = min(kmin, key);
-            kmax = max(kmax, key);
-        }
-        for (int o = 32; o > 0; o >>= 1) {
-            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-        }
-        if (lane == 0) {
-            L.kmin[wave] = kmin;
-            L.kmax[wave] = kmax;
-        }
-        double* H = L.row.hist;
-        for (int b = tid; b < kBins; b += kBlock)
-            H[b] = 0.0;
-        __syncthreads();
-        for (int w = 0; w < kWaves; ++w) {
-            kmin = min(kmin, L.kmin[w]);
-            kmax = max(kmax, L.kmax[w]);
-        }
-        const uint32_t span = C > 0 ? kmax - kmin : 0u;
-        const int nbits = span ? 32 - __clz((int)span) : 1;
-        uint32_t prefix = 0u;
-        double abv = above_total;
-        bool bad = cand_total > (unsigned)kCandCap || !(above_total < need);
-        for (int shift = 11 * ((nbits - 1) / 11); shift >= 0 && !bad; shift -= 11) {
-            for (int i = tid; i < C; i += kBlock) {
-                const float xc = __uint_as_float((unsigned)L.cand[i]);
-                const uint32_t rel = kmax - order_key(xc);
-                if ((uint64_t)rel >> (shift + 11) == prefix)
-                    atomicAdd(&H[rank_slot((rel >> shift) & 0x7ffu)], (double)prob(xc, rs));
-            }
-            __syncthreads();
-            const BinPick pk = wave_pick(H, abv, need, false);
-            // the cut must fall among the candidates
-            if (shift == 11 * ((nbits - 1) / 11) && !(above_total + pk.total >= need))
-                bad = true;
-            prefix = (prefix << 11) | (uint32_t)pk.bin;
-            abv = pk.above;
-            Z = pk.above + pk.in_bin;
-            __syncthreads();
-            if (shift > 0) {
-                for (int b = tid; b < kBins; b += kBlock)
-                    H[b] = 0.0;
-                __syncthreads();
-            }
-        }
-        if (bad) {
-            // candidate overflow or an estimate that missed the cut: redo the row the slow way
-            sample_row_from_memory(sp, r, L.row);
-            return;
-        }
-        key_tau = kmax - prefix;
+    uint32_t key_tau = key_floor;
+    double Z = FILTERED ? s_part : above_total;
+    bool bad = cand_total > (unsigned)kCandCap;
+    if (cut && !bad) {
+        const uint32_t key_cut = radix_select(C, false, above_total, need, bad, Z);
+        key_tau = max(key_tau, key_cut);
+    }
+    if (bad) {
+        // candidate overflow or an estimate that missed the cut: redo the row the slow way
+        sample_row_from_memory(sp, r, L.row);
+        return;
     }
 
     // kept candidates join their segments (vocabulary order)
@@ -1459,7 +1610,7 @@ hipError_t launch_sampler(const SamplerParams& p, void* ws, hipStream_t s)
 {
     const int slices = sampler_slices(p.rows, p.vocab);
     const bool aligned = (p.stride % 4 == 0) && ((uintptr_t)p.logits % 16 == 0);
-    if (slices == 0 || !aligned || p.vocab < 4 || p.top_k || p.min_p) {  // filters: whole-row kernel only
+    if (slices == 0 || !aligned || p.vocab < 4) {
         hipLaunchKernelGGL(sample_rows_kernel, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p);
         return hipGetLastError();
     }
@@ -1467,8 +1618,11 @@ hipError_t launch_sampler(const SamplerParams& p, void* ws, hipStream_t s)
     slice_elems = (slice_elems + 3) / 4 * 4;
     hipLaunchKernelGGL(sampler_scan_kernel, dim3((unsigned)(p.rows * slices)), dim3(kBlock), 0, s, p, (char*)ws, slices,
                        slice_elems);
-    hipLaunchKernelGGL(sampler_finish_kernel, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p, (char*)ws, slices,
+    hipLaunchKernelGGL(sampler_finish_kernel<false>, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p, (char*)ws, slices,
                        slice_elems);
+    if (p.top_k || p.min_p)  // rows with a filter
+        hipLaunchKernelGGL(sampler_finish_kernel<true>, dim3((unsigned)p.rows), dim3(kBlock), 0, s, p, (char*)ws,
+                           slices, slice_elems);
     return hipGetLastError();
 }
 

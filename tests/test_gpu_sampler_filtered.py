@@ -47,6 +47,11 @@ CASES = [
     dict(rows=40, vocab=4099, sigma=6.0, ties=False),
     dict(rows=9, vocab=5, sigma=1.0, ties=True),
     dict(rows=5, vocab=1, sigma=1.0, ties=False),
+    # rows the sliced kernels take (vocabulary a multiple of 4), at a size that fills the chip, and with
+    # bf16-valued logits: exact ties at the k-th element and at the thresholds
+    dict(rows=96, vocab=128256, sigma=3.0, ties=False),
+    dict(rows=24, vocab=50256, sigma=2.0, ties=True),
+    dict(rows=300, vocab=32000, sigma=4.0, ties=True),
 ]
 
 
