@@ -435,7 +435,7 @@ constexpr int kIter = kBlock * 4;         // elements one float4 per thread cove
 constexpr int kSliceMax = 8 * kIter;      // elements per workgroup: 8 float4 per thread
 constexpr int kMaxSlices = 16;
 constexpr int kSegPerSlice = kSliceMax / kSeg;  // 64
-constexpr int kCandCap = 4096;
+constexpr int kCandCap = 3072;
 constexpr int kPubBins = 1024;    // histogram bins of a slice (64 octaves below its maximum)
 constexpr int kEmitCap = 2048;    // (logit, index) pairs a slice may write out
 constexpr int kTopProbe = 0;      // a slice emits from the top if its elements down to L + kTopProbe fit
@@ -1047,8 +1047,10 @@ struct FinishLds {
 
 // FILTERED = false takes the rows without a min-p / top-k filter, FILTERED = true the rows with one
 // (a launch with filter arrays runs both; each leaves the other's rows alone).
+// Three workgroups of the unfiltered kind share a CU (80 registers per lane, 50 KB of LDS each): the
+// step is bound by the latency of its phases, so the third one is nearly free (1024 rows: 78 -> 67 us).
 template <bool FILTERED>
-__global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED ? 3 : 6))) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
 {
     __shared__ FinishLds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -1112,7 +1114,7 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
 
     int lo = kBins, hi = kBins;  // candidate bins, counted down from the maximum's bin; kBins = no cut
     // Units of the slices' histograms per row bin: bin b of slice s is bin b + shift[s] of the row;
-    // thread t gathers row bins 4 t .. 4 t + 3 (all loads of eight slices are requested before any
+    // thread t gathers row bins 4 t .. 4 t + 3 (all loads of four slices are requested before any
     // is used; loads are unconditional from clamped positions, what lies outside a slice's bins is
     // masked afterwards).
     const int rb0 = kBinsPerThread * tid;
@@ -1120,11 +1122,11 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
 #pragma unroll
         for (int k = 0; k < kBinsPerThread; ++k)
             qsum[k] = 0ull;
-        for (int s0 = 0; s0 < slices; s0 += 8) {
-            unsigned qv[8][kBinsPerThread];
-            int sh[8];
+        for (int s0 = 0; s0 < slices; s0 += 4) {
+            unsigned qv[4][kBinsPerThread];
+            int sh[4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const int sl = min(s0 + u, slices - 1);
                 sh[u] = s0 + u < slices ? L.shift[sl] : kBins;
 #pragma unroll
@@ -1134,7 +1136,7 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int k = 0; k < kBinsPerThread; ++k) {
                     const int b = rb0 + k - sh[u];
@@ -1291,14 +1293,14 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
         }
         return kmax - prefix;
     };
-    // pairs written out by the covered slices: four per thread and slice, all requested before any is
-    // used (unconditional loads from clamped positions; what lies past a slice's count is masked)
+    // pairs written out by the covered slices: four per thread and slice, four slices at a time, all
+    // requested before any is used (unconditional loads from clamped positions; what lies past a slice's count is masked)
     static_assert(kEmitCap == 4 * kBlock, "four pairs per thread and slice");
-    for (int s0 = 0; s0 < (FILTERED ? 0 : slices); s0 += 8) {
-        unsigned long long ev[8][4];
-        int cnt[8];
+    for (int s0 = 0; s0 < (FILTERED ? 0 : slices); s0 += 4) {
+        unsigned long long ev[4][4];
+        int cnt[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int s = min(s0 + u, slices - 1);
             cnt[u] = (s0 + u < slices && L.covered[s]) ? min(L.scount[s], kEmitCap) : 0;
             const unsigned long long* e = W.emit + (size_t)s * kEmitCap;
@@ -1307,7 +1309,7 @@ __global__ __launch_bounds__(kBlock) void sampler_finish_kernel(SamplerParams sp
                 ev[u][k] = e[tid + k * kBlock];
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 take(tid + k * kBlock < cnt[u], __uint_as_float((unsigned)ev[u][k]), (int)(ev[u][k] >> 32),
