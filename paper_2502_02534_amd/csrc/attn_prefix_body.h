@@ -336,7 +336,9 @@ __device__ __forceinline__ void prefix_body(const AttnParams& p, const PrefixLev
     // A K fragment is one 128-bit read into `ring`; a V fragment is two 64-bit reads into
     // `ring_lo` / `ring_hi`, put together only after the wait that precedes its MFMA (the wait
     // names all of them as operands, so nothing that reads a fragment register can be placed
-    // before the data has arrived).
+    // before the data has arrived).  What remains an assumption is that the compiler neither copies
+    // nor spills a fragment register between its read and that wait; the kernels built from this
+    // body use no scratch memory, and a host-side test of the build keeps it that way.
     u32x4 ring[kAhead + 2];
     u32x2 ring_lo[kAhead + 2], ring_hi[kAhead + 2];
     auto region = [&](auto qk_tag, auto pv_tag, int kstage, int vstage) __attribute__((always_inline)) {

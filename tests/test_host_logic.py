@@ -72,3 +72,36 @@ def test_prefix_tree_and_its_flattened_form_agree():
 def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_hand_scheduled_attention_kernels_do_not_spill():
+    """The prefix body issues its LDS reads by hand, several fragments ahead of the MFMA that uses
+    them, and orders them with explicit waits; that is sound as long as the compiler neither copies
+    nor spills a fragment register between the read and the wait.  A kernel that has to spill could
+    do so, so the build must keep these kernels free of scratch memory."""
+    import concurrent.futures
+    import re
+    import shutil
+    import subprocess
+    import tempfile
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc")
+    csrc = os.path.join(ROOT, "paper_2502_02534_amd", "csrc")
+
+    def usage(src):
+        with tempfile.TemporaryDirectory() as tmp:
+            out = subprocess.run(
+                [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-munsafe-fp-atomics",
+                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage",
+                 "-c", os.path.join(csrc, src), "-o", os.path.join(tmp, "o.o")],
+                capture_output=True, text=True, check=True).stderr
+        names = re.findall(r"Function Name: (\S+)", out)
+        scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", out)]
+        assert names and len(names) == len(scratch), out[-2000:]
+        return list(zip(names, scratch))
+
+    with concurrent.futures.ThreadPoolExecutor(2) as pool:
+        for kernels in pool.map(usage, ["attn_prefix_mfma.hip", "attn_fused.hip"]):
+            for name, scratch in kernels:
+                assert scratch == 0, (name, scratch)
