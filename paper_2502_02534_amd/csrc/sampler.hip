@@ -1,11 +1,11 @@
 // Temperature / nucleus / inverse-CDF token sampler.
 //
-// Two paths.  The sliced path (below: two stream-ordered kernels, four for launches with many
-// workgroups) reads a row from HBM once, takes a second look that caches serve when the logits
-// fit, and finds the exact nucleus threshold without sorting.  The whole-row routine (one
-// workgroup per row, every pass from memory) covers what the sliced path does not take: unaligned
-// rows, vocabularies beyond 16 slices, the rare row whose candidate set overflows, and rows with
-// a min-p or top-k filter.
+// Two paths.  The sliced path (below: two stream-ordered kernels) reads a row from HBM once, leaves
+// what the row-level step needs in the workspace, and finds the exact nucleus threshold without
+// sorting.  The whole-row routine (one workgroup per row, every pass from memory) covers what the
+// sliced path does not take: unaligned rows, vocabularies beyond 16 slices, the rare row whose
+// candidate set overflows, and rows whose min-p or top-k filter reaches further down than the
+// sliced path's windows.
 //
 // Probabilities are evaluated by one shared routine, p_i = 2^((x_i - max) c) with
 // c = log2(e)/T carried as hi + lo floats, so every pass sees the same bits; every sum that
@@ -428,6 +428,10 @@ __device__ void sample_row_from_memory(const SamplerParams& sp, long long r, Row
 //           threshold is found among the candidates by radix select on the logit's bit pattern
 //           with fp64 masses; kept candidates join their segments; the segments are scanned and
 //           the walk ends inside the segment that contains u * Z.
+//           Rows with a min-p or top-k filter (a second instantiation of the kernel, launched
+//           beside the first when filter arrays are given): the scan kernel writes such a row out
+//           from the top as far as the budget goes, and the survivors of the filters, found among
+//           the pairs, become the candidate list.
 //
 // With the row statistics exchanged through memory between two kernels, plain stores and loads do.
 // =============================================================================================
