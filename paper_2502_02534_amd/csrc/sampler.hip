@@ -585,7 +585,8 @@ constexpr int kWaveStage = kEmitCap / kWaves * 2;  // pairs one wavefront may ga
 struct ScanLds {
     unsigned hist[kPubBins + 64];       // + one place per lane for what lies past the last bin
     unsigned cumq[kPubBins];            // inclusive running sum of hist
-    unsigned long long stage[kWaves][kWaveStage];  // each wavefront's pairs, copied out in one piece
+    unsigned long long stage[kWaves][kWaveStage + 1];  // each wavefront's pairs, copied out in one piece (+ one
+                                                       // place that takes whatever does not fit)
     double wave_mass[kWaves];
     unsigned wave_q[kWaves];
     float red_f[kWaves];
@@ -605,13 +606,17 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Fixed-point mass of a logit inside its bin: 32768 2^(f/16) for f in [0, 1), as a cubic in f
-// (the next term of the series is below 0.005 units).  NaN (positions past the end of a slice)
-// converts to 0.
+// Fixed-point mass of a logit inside its bin: 32768 2^(f/16) for f in [0, 1), as a quadratic in f:
+// the series 32768 + a1 f + a2 f^2 + a3 f^3 with f^3 replaced by its best quadratic on [0, 1],
+// (48 f^2 - 18 f + 1) / 32 (error a3 / 32 = 0.014 units; the next term of the series is below
+// 0.005).  Values run from 32768 to 34219.  NaN (positions past the end of a slice) converts to 0.
+// The scan kernel's pass over the logits is bound by its vector instructions (every instruction
+// per logit costs it about 2 % of its time), hence the count of every one here and below.
 __device__ __forceinline__ unsigned bin_units(float f)
 {
     const float a1 = 1419.5653f, a2 = 30.749034f, a3 = 0.44403f;
-    return (unsigned)__builtin_fmaf(__builtin_fmaf(__builtin_fmaf(a3, f, a2), f, a1), f, 32768.5f);
+    const float b0 = 32768.5f + a3 / 32.f, b1 = a1 - a3 * (18.f / 32.f), b2 = a2 + a3 * (48.f / 32.f);
+    return (unsigned)__builtin_fmaf(__builtin_fmaf(b2, f, b1), f, b0);
 }
 
 __device__ __forceinline__ int wave_max_i32(int v)
@@ -771,12 +776,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
     // maximum belong to the last bin; each lane collects them in a place of its own (they would
     // otherwise all meet at one LDS address) and the places are added to the last bin afterwards.
     // Positions past the end of the slice (-inf) land there too, with zero units. ----
-    const float far_slot = (float)(kPubBins + lane);
+    // (byte offsets: four times the bin, formed in floating point, so that one conversion gives
+    // the LDS address; what lands between the last bin and the lane's own place belongs to the
+    // last bin all the same)
+    const float far4 = (float)(4 * (kPubBins + lane)), kf_loc4 = 4.f * kf_loc;
     auto bin_one = [&](float xq) __attribute__((always_inline)) {
         const float t = xq * rc.c16;
         const float kf = floorf(t);
-        const float bf = kf_loc - kf;  // >= 0: kf_loc belongs to the maximum
-        atomicAdd(&L.hist[(int)(bf < (float)(kPubBins - 1) ? bf : far_slot)], bin_units(t - kf));
+        const float off = fminf(__builtin_fmaf(kf, -4.f, kf_loc4), far4);  // >= 0: kf_loc belongs to the maximum
+        atomicAdd((unsigned*)((char*)L.hist + (unsigned)off), bin_units(t - kf));
     };
 #pragma unroll
     for (int q = 0; q < 32; ++q)
@@ -883,32 +891,40 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) voi
     // ---- the pairs: every wavefront gathers its own in LDS (the lanes that hold one take consecutive
     // places), reserves as many places in the slice's list and copies them out in one piece ----
     int have = 0;  // pairs this wavefront has gathered (uniform)
-    auto gather = [&](bool pred, float xq, int idx) __attribute__((always_inline)) {
-        const unsigned long long mask = __ballot(pred);
-        if (mask != 0ull) {
-            if (pred) {
-                const int pos = have + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
-                                                                       __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
-                if (pos < kWaveStage)
-                    L.stage[wave][pos] = (unsigned long long)__float_as_uint(xq) | ((unsigned long long)(unsigned)idx << 32);
-            }
-            have += __popcll(mask);
+    // (one compare, two lane counts that also add the running total, a clamp, the index, the address;
+    // logit and index go out of two registers with one two-dword write)
+    const unsigned stage_base = (unsigned)(size_t)(__attribute__((address_space(3))) void*)&L.stage[wave][0];
+    auto gather = [&](unsigned long long mask /* the wavefront's ballot of pred */, bool pred, float xq,
+                      int idx) __attribute__((always_inline)) {
+        if (pred) {
+            const int pos = min((int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                               __builtin_amdgcn_mbcnt_lo((unsigned)mask, (unsigned)have)),
+                                kWaveStage);
+            const unsigned addr = stage_base + 8u * (unsigned)pos;
+            asm volatile("ds_write2_b32 %0, %1, %2 offset1:1" ::"v"(addr), "v"(xq), "v"(idx) : "memory");
         }
+        have += __popcll(mask);
     };
     if (win_hi >= 0) {
         if (win_lo <= 0) {
 #pragma unroll
-            for (int q = 0; q < 32; ++q)
-                gather(xv[q] * rc.c16 >= t_emit, xv[q], g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
+            for (int q = 0; q < 32; ++q) {
+                const bool in = xv[q] * rc.c16 >= t_emit;
+                gather(__builtin_amdgcn_ballot_w64(in), in, xv[q], g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
+            }
         } else {
 #pragma unroll
             for (int q = 0; q < 32; ++q) {
                 const float t = xv[q] * rc.c16;
-                gather(t >= t_emit && t < t_above, xv[q], g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
+                const bool in = t >= t_emit, below = t < t_above;  // (two ballots and a scalar AND: no vector work)
+                gather(__builtin_amdgcn_ballot_w64(in) & __builtin_amdgcn_ballot_w64(below), in && below, xv[q],
+                       g.e0 + (q >> 2) * kIter + tid * 4 + (q & 3));
             }
         }
-        for (int k = 0; k < 3; ++k)
-            gather(tail[k] * rc.c16 >= t_emit, tail[k], g.v4end + k);  // (-inf where there is no tail logit)
+        for (int k = 0; k < 3; ++k) {
+            const bool in = tail[k] * rc.c16 >= t_emit;  // (-inf where there is no tail logit)
+            gather(__builtin_amdgcn_ballot_w64(in), in, tail[k], g.v4end + k);
+        }
     }
     int base = 0;
     if (lane == 0 && have) {
