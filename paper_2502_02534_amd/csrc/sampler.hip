@@ -1216,8 +1216,22 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED
     // lanes of a wavefront take consecutive places reserved with one counter update); else dropped.
     // Called by whole wavefronts (`live` masks lanes that hold nothing).
     float f_part = 0.f;  // exact mass of the elements taken since the last widening
+    // (the lane's place among the wavefront's candidates comes from the two lane-count instructions)
+    auto append_masked = [&](unsigned long long mask, bool want, unsigned long long pair) __attribute__((always_inline)) {
+        if (mask != 0ull) {
+            unsigned base = 0u;
+            if (lane == 0)
+                base = atomicAdd(&L.cand_total, (unsigned)__popcll(mask));
+            base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+            if (want) {
+                const unsigned pos = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, base));
+                if (pos < (unsigned)kCandCap)
+                    L.cand[pos] = pair;
+            }
+        }
+    };
     auto take = [&](bool live, float xq, int idx, int s) __attribute__((always_inline)) {
-        if (__ballot(live) == 0ull)
+        if (__builtin_amdgcn_ballot_w64(live) == 0ull)
             return;  // nothing in this wavefront's 64 places
         const float t = xq * rc.c16;
         const bool above = live && t >= t_above;
@@ -1225,34 +1239,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED
         const float pq = live ? prob(xq, rs) : 0.f;
         f_part += pq;
         if (above)
-            atomicAdd(&seg_mass[s * kSegPerSlice + (idx - s * slice_elems) / kSeg], (double)pq);
-        const unsigned long long mask = __ballot(candq);
-        if (mask != 0ull) {
-            unsigned base = 0u;
-            if (lane == 0)
-                base = atomicAdd(&L.cand_total, (unsigned)__popcll(mask));
-            base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
-            if (candq) {
-                const unsigned pos = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
-                if (pos < (unsigned)kCandCap)
-                    L.cand[pos] = (unsigned long long)__float_as_uint(xq) | ((unsigned long long)(unsigned)idx << 32);
-            }
-        }
+            atomicAdd(&seg_mass[s * kSegPerSlice + (int)((unsigned)(idx - s * slice_elems) / (unsigned)kSeg)], (double)pq);
+        append_masked(__builtin_amdgcn_ballot_w64(candq), candq,
+                      (unsigned long long)__float_as_uint(xq) | ((unsigned long long)(unsigned)idx << 32));
     };
     // One wavefront-wide append to the candidate list.
     auto append = [&](bool want, unsigned long long pair) __attribute__((always_inline)) {
-        const unsigned long long mask = __ballot(want);
-        if (mask != 0ull) {
-            unsigned base = 0u;
-            if (lane == 0)
-                base = atomicAdd(&L.cand_total, (unsigned)__popcll(mask));
-            base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
-            if (want) {
-                const unsigned pos = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
-                if (pos < (unsigned)kCandCap)
-                    L.cand[pos] = pair;
-            }
-        }
+        append_masked(__builtin_amdgcn_ballot_w64(want), want, pair);
     };
     // Radix select over the order keys of the first C candidates, taken relative to the largest one
     // (rel = kmax - key, 0 = most probable) so that only the bits in which the candidates differ
