@@ -1070,7 +1070,7 @@ struct FinishLds {
 // Three workgroups of the unfiltered kind share a CU (80 registers per lane, 50 KB of LDS each): the
 // step is bound by the latency of its phases, so the third one is nearly free (1024 rows: 78 -> 67 us).
 template <bool FILTERED>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED ? 3 : 6))) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED ? 4 : 6))) void sampler_finish_kernel(SamplerParams sp, char* ws, int slices, int slice_elems)
 {
     __shared__ FinishLds L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
