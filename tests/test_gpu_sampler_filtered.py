@@ -52,6 +52,8 @@ CASES = [
     dict(rows=96, vocab=128256, sigma=3.0, ties=False),
     dict(rows=24, vocab=50256, sigma=2.0, ties=True),
     dict(rows=300, vocab=32000, sigma=4.0, ties=True),
+    # more than eight slices per row: rows with a filter leave the sliced kernels for the whole-row routine
+    dict(rows=6, vocab=200004, sigma=3.0, ties=False),
 ]
 
 
