@@ -15,7 +15,9 @@
 //                 same 16-byte column slice of 8 token rows and turns it into 8
 //                 token-contiguous fragments)
 //
-// Global loads are 16 bytes per lane; for V 16 adjacent lanes cover one 256-byte row.
+// Global loads are 16 bytes per lane; for V 16 adjacent lanes cover one 256-byte row.  A whole
+// tile is loaded from uniform bases plus per-lane offsets that are fixed for the chunk, so its
+// sixteen loads cost no vector arithmetic; only a chunk's last, ragged tile clamps its rows.
 // The next tile's loads are issued before the current tile is computed, and with paged KV the
 // page numbers of the tile after that are fetched at the same time, so that no KV load waits
 // for a page-table load.  The body uses no LDS.
@@ -109,15 +111,6 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
         }
         return tp;
     };
-    // uint4 index of (token t of this sample, head j, 16-byte piece 0); t lies in the tile at tb
-    auto row_index = [&](int t, int tb, const TilePages& tp) -> long long {
-        if (PAGED) {
-            const long long pg = (t >> 4) == (tb >> 4) ? tp.a : tp.b;
-            return ((pg * p.Hkv + j) * 16 + (t & 15)) * kRow;
-        }
-        return (((long long)n * p.max_suffix_len + t) * p.Hkv + j) * kRow;
-    };
-
     // Query fragments: B operand, column n = query head j*G + c (zero beyond G),
     // k-slot (step s, lane-row r) = channels 32 s + 8 r .. + 7.
     bf16x8 qf[4];
@@ -135,18 +128,53 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
     // K: register 4 blk + s of lane (c, r) = token 16 blk + c, channels 32 s + 8 r .. + 7 (the A operand of
     // step s for token block blk).  V: register s of lane (r, c) = token tile_token(r, s), 16-byte piece c.
     // Tokens past the end of the chunk are clamped to its last one (their scores are masked).
+    // A whole tile is loaded from uniform bases (the tile's first row of this KV head; with paged KV
+    // the first row of each of its two pages) plus 32-bit lane offsets fixed for the whole chunk,
+    // so that a load costs no address arithmetic in the vector ALU; only the last, ragged tile of a
+    // chunk takes the general path with its clamps.
+    const unsigned row_bytes = PAGED ? 256u : (unsigned)p.Hkv * 256u;   // from one token row of the head to the next
+    const unsigned koff = (unsigned)c * row_bytes + 16u * (unsigned)r;  // token c of a 16-token block, piece r (+ 64 s)
+    const unsigned voff = (unsigned)(4 * r) * row_bytes + 16u * (unsigned)c;  // token 4 r (+ s rows), piece c
     uint4 kreg[8], vreg[8];
     auto load_tile = [&](int tb, const TilePages& tp, uint4 (&kk)[8], uint4 (&vv)[8]) __attribute__((always_inline)) {
+        // row (of this KV head) of the tile's tokens 0 .. 15 and 16 .. 31, in units of 256 bytes
+        const long long first = PAGED ? (tp.a * p.Hkv + j) * 16 : ((long long)n * p.max_suffix_len + tb) * p.Hkv + j;
+        const long long second = PAGED ? (tp.b * p.Hkv + j) * 16 : first + 16ll * p.Hkv;
+        const int last = t1 - 1 - tb;  // the tile's last valid token (uniform, >= 0)
+        if (last >= kTile - 1) {
+            const char* ka = (const char*)kg + first * 256;
+            const char* kb = (const char*)kg + second * 256;
+            const char* va = (const char*)vg + first * 256;
+            const char* vb = (const char*)vg + second * 256;
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            const long long kidx = row_index(min(tb + 16 * blk + c, t1 - 1), tb, tp);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                kk[4 * blk + s] = kg[kidx + 4 * s + r];
+            for (int s = 0; s < 4; ++s) {
+                kk[s] = *reinterpret_cast<const uint4*>(ka + koff + 64 * s);
+                kk[4 + s] = *reinterpret_cast<const uint4*>(kb + koff + 64 * s);
+                // V register s holds token 4 r + s, register 4 + s token 16 + 4 r + s
+                vv[s] = *reinterpret_cast<const uint4*>(va + (size_t)s * row_bytes + voff);
+                vv[4 + s] = *reinterpret_cast<const uint4*>(vb + (size_t)s * row_bytes + voff);
+            }
+            return;
         }
+        // the ragged last tile of a chunk: tokens past the end are clamped to the last one (their
+        // scores are masked, and what is multiplied by their zero weights must be finite)
+        const bool two = last >= 16;  // the second half holds valid tokens
+        const long long sec = two ? second : first;
+        const int last0 = two ? 15 : last, last1 = two ? last - 16 : last;  // clamps inside each half
+        const char* ka = (const char*)kg + first * 256;
+        const char* kb = (const char*)kg + sec * 256;
+        const char* va = (const char*)vg + first * 256;
+        const char* vb = (const char*)vg + sec * 256;
+        const unsigned k0 = (unsigned)min(c, last0) * row_bytes + 16u * (unsigned)r;
+        const unsigned k1 = (unsigned)(two ? min(c, last1) : last1) * row_bytes + 16u * (unsigned)r;
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-            vv[s] = vg[row_index(min(tb + tile_token(r, s), t1 - 1), tb, tp) + c];
+        for (int s = 0; s < 4; ++s) {
+            kk[s] = *reinterpret_cast<const uint4*>(ka + k0 + 64 * s);
+            kk[4 + s] = *reinterpret_cast<const uint4*>(kb + k1 + 64 * s);
+            vv[s] = *reinterpret_cast<const uint4*>(va + (unsigned)min(4 * r + s, last0) * row_bytes + 16u * (unsigned)c);
+            vv[4 + s] = *reinterpret_cast<const uint4*>(vb + (unsigned)(two ? min(4 * r + s, last1) : last1) * row_bytes +
+                                                        16u * (unsigned)c);
+        }
     };
 
     float m_run = -INFINITY;  // running maximum of query head c (replicated over lane-rows)
@@ -156,18 +184,13 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
     for (int i = 0; i < 8; ++i)
         o[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    load_tile(t0, tile_pages(t0), kreg, vreg);
+    // One tile: the next tile's loads go out first (into `knext` / `vnext`), then the scores, the
+    // online softmax and P V of the tile held in `kcur` / `vcur`.  (Two register sets in swapped
+    // roles, with the loop unrolled by two, would save the copy at the end of a round, but need
+    // more registers than two wavefronts per SIMD leave.)
     TilePages pages_next = tile_pages(min(t0 + kTile, t1 - 1) & ~(kTile - 1));
-
-    for (int tb = t0; tb < t1; tb += kTile) {
-        const bool more = tb + kTile < t1;
-        uint4 knext[8], vnext[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            knext[s] = make_uint4(0, 0, 0, 0);
-            vnext[s] = make_uint4(0, 0, 0, 0);
-        }
-        if (more) {
+    auto tile_step = [&](int tb, uint4 (&kcur)[8], uint4 (&vcur)[8], uint4 (&knext)[8], uint4 (&vnext)[8]) __attribute__((always_inline)) {
+        if (tb + kTile < t1) {
             load_tile(tb + kTile, pages_next, knext, vnext);
             pages_next = tile_pages(min(tb + 2 * kTile, t1 - 1) & ~(kTile - 1));
         }
@@ -179,7 +202,7 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
             sacc[blk] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[4 * blk + s]), qf[s], sacc[blk], 0, 0, 0);
+                sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kcur[4 * blk + s]), qf[s], sacc[blk], 0, 0, 0);
             }
         }
         // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c;
@@ -231,20 +254,28 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
         for (int i = 0; i < 8; ++i) {
             const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
             uint4 f;
-            f.x = __builtin_amdgcn_perm(dword(vreg[1], i >> 1), dword(vreg[0], i >> 1), sel);
-            f.y = __builtin_amdgcn_perm(dword(vreg[3], i >> 1), dword(vreg[2], i >> 1), sel);
-            f.z = __builtin_amdgcn_perm(dword(vreg[5], i >> 1), dword(vreg[4], i >> 1), sel);
-            f.w = __builtin_amdgcn_perm(dword(vreg[7], i >> 1), dword(vreg[6], i >> 1), sel);
+            f.x = __builtin_amdgcn_perm(dword(vcur[1], i >> 1), dword(vcur[0], i >> 1), sel);
+            f.y = __builtin_amdgcn_perm(dword(vcur[3], i >> 1), dword(vcur[2], i >> 1), sel);
+            f.z = __builtin_amdgcn_perm(dword(vcur[5], i >> 1), dword(vcur[4], i >> 1), sel);
+            f.w = __builtin_amdgcn_perm(dword(vcur[7], i >> 1), dword(vcur[6], i >> 1), sel);
             // column c of this MFMA is channel 8 c + i
             o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf, as_bf16x8(f), o[i], 0, 0, 0);
         }
+    };
 
-        if (more) {
+    load_tile(t0, tile_pages(t0), kreg, vreg);
+    for (int tb = t0; tb < t1; tb += kTile) {
+        uint4 knext[8], vnext[8];
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                kreg[s] = knext[s];
-                vreg[s] = vnext[s];
-            }
+        for (int s = 0; s < 8; ++s) {
+            knext[s] = make_uint4(0, 0, 0, 0);
+            vnext[s] = make_uint4(0, 0, 0, 0);
+        }
+        tile_step(tb, kreg, vreg, knext, vnext);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            kreg[s] = knext[s];
+            vreg[s] = vnext[s];
         }
     }
 
