@@ -208,15 +208,23 @@ __device__ __forceinline__ void suffix_body(const AttnParams& p, int slot0, long
         // lane (c, r) register (blk, i) = score of token tb + 16 blk + 4 r + i for head c;
         // scores stay unscaled, the scale is folded into the exponent: p = 2^(s * scale - m)
         float sv[8];
-        float tmax = -INFINITY;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = tb + 16 * blk + 4 * r + i;
-                sv[4 * blk + i] = t < t1 ? sacc[blk][i] : -INFINITY;
-                tmax = fmaxf(tmax, sv[4 * blk + i]);
-            }
+            for (int i = 0; i < 4; ++i)
+                sv[4 * blk + i] = sacc[blk][i];
+        if (tb + kTile > t1) {  // only the last tile of a chunk can be ragged
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (tb + 16 * blk + 4 * r + i >= t1)
+                        sv[4 * blk + i] = -INFINITY;
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            tmax = fmaxf(tmax, sv[i]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float m_new = fmaxf(m_run, tmax * p.scale_log2);  // finite: the tile holds a valid token

@@ -7,7 +7,7 @@ namespace {
 using namespace suffix_impl;
 
 template <bool PAGED>
-__global__ __launch_bounds__(256) void attn_suffix_mfma_kernel(AttnParams p, int slot0)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_suffix_mfma_kernel(AttnParams p, int slot0)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     suffix_body<PAGED>(p, slot0, (long long)blockIdx.x * kWavesPerBlock + wave);
