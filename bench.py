@@ -17,6 +17,7 @@ bounds it.  `cpu_baseline` is the fp64 checker timed on the host cores on a
 bounded sample of the same workload (a reported baseline, not a target).
 """
 import argparse
+import dataclasses
 import hashlib
 import json
 import os
@@ -83,6 +84,8 @@ def main() -> int:
                     help="skip the other configurations measured beside the main one (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an elementwise kernel over 256 MiB three times (reference for HBM traffic counters)")
+    ap.add_argument("--page-order", choices=["shuffled", "sequential"], default="shuffled",
+                    help="paged workloads: page table dealt out at random (the default recipe) or in order of use")
     ap.add_argument("--print-source-hashes", action="store_true",
                     help="print the source hash of every timed kernel (for profiles/hbm_traffic_table.txt) and exit")
     args = ap.parse_args()
@@ -121,7 +124,9 @@ def main() -> int:
     def whole_step(cfg: int, steps: int, warmup: int):
         """Uploads configuration `cfg` and times `steps` whole steps; returns (ms per step, context)."""
         sp = workloads.SPECS[cfg]
-        layers_host = [workloads.make_attn_inputs(cfg, layer=l) for l in range(sp.layers)]
+        if sp.page_size and args.page_order != sp.page_order:
+            sp = dataclasses.replace(sp, page_order=args.page_order)
+        layers_host = [workloads.make_attn_inputs(cfg, layer=l, spec=sp) for l in range(sp.layers)]
         sin = workloads.make_sampler_inputs(cfg)
         elt = 2 if sp.dtype == "bf16" else 4
         first = layers_host[0]
@@ -219,7 +224,8 @@ def main() -> int:
     }
     for name, k in kernels.items():
         k["frac_hbm_peak"] = k.get("GBps", 0.0) / HBM_PEAK_GBS
-        k["traffic"] = measured_traffic(name, sp.name)
+        # the counters were taken on the recipe's own page table
+        k["traffic"] = measured_traffic(name, sp.name) if sp.page_order == workloads.SPECS[args.config].page_order else None
     kernels["prefix"]["frac_mfma_peak"] = kernels["prefix"]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
     # the dominant kernel is looked for among the stages that are one kernel each
     per_step = {k: v["us"] * v["calls_per_step"] for k, v in kernels.items()
@@ -334,6 +340,8 @@ def main() -> int:
               "q_heads": sp.num_q_heads, "kv_heads": sp.num_kv_heads, "head_dim": sp.head_dim,
               "prefix_tokens": int(first.prefix_lens.sum()), "suffix_tokens": int(first.suffix_lens.sum()),
               "vocab": sp.vocab, "layers": sp.layers, "page_size": sp.page_size, "input_copies_rotated": copies}
+    if sp.page_size:
+        config["page_order"] = sp.page_order
 
     # ---- the other configurations: whole-step rate only ------------------------------------------------
     also = {}

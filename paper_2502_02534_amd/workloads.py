@@ -46,6 +46,7 @@ class WorkloadSpec:
     boosted: int = 0          # tokens per row that get +boost
     boost: float = 0.0
     layers: int = 1
+    page_order: str = "shuffled"   # paged KV: "shuffled" = pages dealt out at random, "sequential" = in order of use
 
     @property
     def num_samples(self) -> int:
@@ -184,6 +185,8 @@ def make_attn_inputs(cfg: int, layer: int = 0, *, spec: Optional[WorkloadSpec] =
     spg = (suffix_lens.astype(np.int64) + P - 1) // P
     num_pages = int(pp.sum() + spg.sum())
     perm = r_perm.permutation(num_pages).astype(np.int32)
+    if sp.page_order == "sequential":
+        perm = np.arange(num_pages, dtype=np.int32)
     prefix_indptr = np.concatenate([[0], np.cumsum(pp)]).astype(np.int32)
     suffix_page_indptr = np.concatenate([[0], np.cumsum(spg)]).astype(np.int32)
     prefix_page_indices = perm[: int(pp.sum())].copy()
