@@ -53,6 +53,20 @@ def test_paged_layout_bookkeeping():
     assert used.max() < inp.k_prefix.shape[0]
 
 
+def test_pages_in_order_of_use_differ_from_the_shuffled_table_only_in_the_table():
+    import dataclasses
+    spec = W.small_spec(dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=3,
+                        samples_per_prompt=4, prefix_len=(1, 100), suffix_len=(0, 50), page_size=16)
+    a = W.make_attn_inputs(0, spec=spec, seed=9)
+    b = W.make_attn_inputs(0, spec=dataclasses.replace(spec, page_order="sequential"), seed=9)
+    used = np.concatenate([b.prefix_page_indices, b.suffix_page_indices])
+    assert np.array_equal(used, np.arange(len(used)))   # handed out in order of use
+    assert not np.array_equal(a.prefix_page_indices, b.prefix_page_indices)
+    for x, y in ((a.q, b.q), (a.k_prefix, b.k_prefix), (a.prefix_lens, b.prefix_lens), (a.suffix_lens, b.suffix_lens),
+                 (a.prefix_indptr, b.prefix_indptr), (a.suffix_page_indptr, b.suffix_page_indptr)):
+        assert np.array_equal(x, y)
+
+
 def test_prefix_tree_and_its_flattened_form_agree():
     c = W.make_cascade_inputs([[6], [2, 4], [1, 1, 2, 2]], [(5, 5), (0, 7), (1, 3)], suffix_len=(0, 4), seed=3)
     flat = c.flat
