@@ -1,12 +1,15 @@
 """GPU parity at the full sizes of configurations 3, 4 and 5, in the launch configuration the
 benchmark times.  Attention: configuration 3 is compared on every output row; 4 and 5 on a
 seeded sample of rows the fp64 checker computes one by one (plus every structurally special
-row: empty suffixes, the shortest and longest sequences).  The sampler is compared on every row.
+row: empty suffixes, the shortest and longest sequences), and all three on every row with inputs
+whose result follows from the lengths alone (zero keys, owner-coded values).  The sampler is
+compared on every row.
 Tolerances: tests/gpu_checks.py."""
 import numpy as np
 import pytest
 
 from gpu_checks import attention_errors, check_attention, check_tokens, lse_errors
+from owner_coded_inputs import ownership_problem
 from paper_2502_02534_amd import workloads as W
 
 torch = pytest.importorskip("torch")
@@ -106,3 +109,30 @@ def test_very_long_sequences(dev, oracle, kw):
     lse = d.lse.cpu().numpy().astype(np.float64).reshape(-1)[rows]
     attention_errors(got, ref, "bf16")
     lse_errors(lse, ref_lse, "bf16")
+
+
+# ---- every row of the full configurations, without the checker (tests/owner_coded_inputs.py) ------
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_every_row_averages_its_own_tokens_and_counts_them(dev, cfg):
+    print(f"config {cfg}: zero keys, owner-coded values, every row", flush=True)
+    inp = W.make_attn_inputs(cfg)
+    expect, expect_lse = ownership_problem(inp)
+    d = dev.upload_attn(inp)
+    d.out.fill_(float("nan"))
+    d.lse.fill_(float("nan"))
+    d.run()
+    torch.cuda.synchronize()
+    got = d.out.float().cpu().numpy().astype(np.float64)
+    lse = d.lse.cpu().numpy().astype(np.float64)
+    del d
+    torch.cuda.empty_cache()
+    assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
+    zero = expect == 0
+    assert np.all(got[zero] == 0), f"{int((got[zero] != 0).sum())} channels hold a foreign value row"
+    # half a unit in the last place of the bf16 result (up to 2^-8 of the value) and of the fp16
+    # partial states (2^-11); the sums themselves are exact (ones and zeros in fp32)
+    rel = np.abs(got[~zero] - expect[~zero]) / expect[~zero]
+    assert rel.max() <= 2.0 ** -8 + 2.0 ** -10, rel.max()
+    assert np.abs(lse - expect_lse).max() <= 2e-5, np.abs(lse - expect_lse).max()
+    print(f"  rows {got.shape[0] * got.shape[1]}: max rel err {rel.max():.2e}, "
+          f"max lse err {np.abs(lse - expect_lse).max():.2e}", flush=True)

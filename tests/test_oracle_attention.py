@@ -288,3 +288,18 @@ def test_row_subset_matches_full(oracle):
     o2, l2 = oracle.attention_inputs(inp, rows=rows)
     np.testing.assert_array_equal(o2, out.reshape(-1, 64)[rows])
     np.testing.assert_array_equal(l2, lse.reshape(-1)[rows])
+
+
+@pytest.mark.parametrize("page_size", [0, 16])
+def test_zero_keys_and_owner_coded_values_pin_the_bookkeeping(oracle, page_size):
+    """Zero keys make the softmax uniform: every row is the mean of its own value rows and its
+    log-sum-exp the logarithm of its token count (tests/owner_coded_inputs.py).  A wrong page, a
+    wrong sample slot, a wrong KV head or a miscounted length in the checker fails here."""
+    from owner_coded_inputs import ownership_problem
+    spec = W.small_spec(dtype="bf16", num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=3,
+                        samples_per_prompt=4, prefix_len=(1, 100), suffix_len=(0, 50), page_size=page_size)
+    inp = W.make_attn_inputs(0, spec=spec, seed=9)
+    expect, expect_lse = ownership_problem(inp)
+    ref, ref_lse = oracle.attention_inputs(inp)
+    assert np.abs(ref.reshape(expect.shape) - expect).max() <= 1e-14
+    assert np.abs(ref_lse.reshape(expect_lse.shape) - expect_lse).max() <= 1e-14
