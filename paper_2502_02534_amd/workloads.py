@@ -294,7 +294,20 @@ def make_cascade_inputs(group_sizes, len_ranges, *, dtype="bf16", num_q_heads=8,
     r_ks, r_vs = r_s.spawn(2)
     k_suffix = _normal(r_ks, (N, max(ls_max, 1), Hkv, D), dtype)
     v_suffix = _normal(r_vs, (N, max(ls_max, 1), Hkv, D), dtype)
-    # the same problem as one level: cut the samples wherever any level starts a new group
+    inp = CascadeInputs(None, q, levels, k_suffix, v_suffix, suffix_lens, max(ls_max, 1), None)
+    flatten_cascade(inp, suffix_len)
+    return inp
+
+
+def flatten_cascade(inp: CascadeInputs, suffix_len=None) -> None:
+    """(Re)writes `inp.flat` and `inp.spec` from the levels: the same problem as one level, the samples
+    cut wherever any level starts a new group.  Call it again after editing the levels' KV."""
+    q, levels = inp.q, inp.levels
+    _, Hq, D = q.shape
+    Hkv = levels[0].k.shape[1]
+    dtype = "bf16" if q.dtype == np.uint16 else "f32"
+    if suffix_len is None:
+        suffix_len = inp.spec.suffix_len
     cuts = sorted(set(int(c) for lv in levels for c in lv.sample_indptr))
     flat_k, flat_v, flat_lens = [], [], []
     for a in cuts[:-1]:
@@ -313,8 +326,7 @@ def make_cascade_inputs(group_sizes, len_ranges, *, dtype="bf16", num_q_heads=8,
     spec = small_spec(dtype=dtype, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, num_prompts=len(sizes_flat),
                       samples_per_prompt=int(sizes_flat.max()), prefix_len=(0, int(max(flat_lens.max(), 1))),
                       suffix_len=suffix_len)
-    spec = dataclasses.replace(spec, name="cascade")
-    flat = AttnInputs(spec, q, fk, fv, flat_lens, np.concatenate([[0], np.cumsum(flat_lens)]).astype(np.int32),
-                      np.asarray(cuts, dtype=np.int32), k_suffix, v_suffix, suffix_lens, max(ls_max, 1),
-                      int(max(flat_lens.max(), 1)))
-    return CascadeInputs(spec, q, levels, k_suffix, v_suffix, suffix_lens, max(ls_max, 1), flat)
+    inp.spec = dataclasses.replace(spec, name="cascade")
+    inp.flat = AttnInputs(inp.spec, q, fk, fv, flat_lens, np.concatenate([[0], np.cumsum(flat_lens)]).astype(np.int32),
+                          np.asarray(cuts, dtype=np.int32), inp.k_suffix, inp.v_suffix, inp.suffix_lens,
+                          inp.max_suffix_len, int(max(flat_lens.max(), 1)))

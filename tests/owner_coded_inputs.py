@@ -84,3 +84,72 @@ def ownership_problem(inp):
             row[49] = f[n]
             expect[n, j * G:(j + 1) * G] = row
     return expect, np.repeat(np.log(lp + ls)[:, None], sp.num_q_heads, axis=1)
+
+
+def ownership_tree_problem(inp):
+    """The same for a tree of shared prefixes (`workloads.CascadeInputs`, bf16, at most four levels
+    of at most 1024 groups, fewer than 2048 samples): overwrites the levels' and the suffixes' K and V
+    and rewrites the flattened form; returns (expected output, expected lse).
+
+    Channels: level l owns 21 (10 bits of the group, their complements, one flag), the suffix 23
+    (11 bits of the sample, complements, flag) from channel 84 on, the KV head 6 from channel 107."""
+    from paper_2502_02534_amd import workloads as W
+    q, levels = inp.q, inp.levels
+    N, Hq, D = q.shape
+    Hkv = levels[0].k.shape[1]
+    G = Hq // Hkv
+    assert q.dtype == np.uint16 and D == 128 and len(levels) <= 4 and N < 2048 and Hkv <= 8
+    as_bf16 = lambda c: np.where(c != 0, _ONE, np.uint16(0)).astype(np.uint16)
+
+    def head_part(j):
+        c = np.zeros(128)
+        c[107:113] = _bits(j, 3)
+        return c
+
+    def level_code(l, g, j):
+        c = head_part(j)
+        c[21 * l:21 * l + 20] = _bits(g, 10)
+        c[21 * l + 20] = 1.0
+        return c
+
+    def suffix_code(n, j):
+        c = head_part(j)
+        c[84:106] = _bits(n, 11)
+        c[106] = 1.0
+        return c
+
+    for l, lv in enumerate(levels):
+        assert len(lv.lens) <= 1024
+        lv.k[...] = 0
+        for g in range(len(lv.lens)):
+            for j in range(Hkv):
+                lv.v[lv.indptr[g]:lv.indptr[g] + lv.lens[g], j] = as_bf16(level_code(l, g, j))
+    inp.k_suffix[...] = _NAN
+    inp.v_suffix[...] = _NAN
+    for n in range(N):
+        ls = int(inp.suffix_lens[n])
+        inp.k_suffix[n, :ls] = 0
+        for j in range(Hkv):
+            inp.v_suffix[n, :ls, j] = as_bf16(suffix_code(n, j))
+    W.flatten_cascade(inp)
+
+    expect = np.zeros((N, Hq, 128))
+    total = inp.suffix_lens.astype(np.float64).copy()
+    group_of = []
+    for lv in levels:
+        g = np.searchsorted(lv.sample_indptr, np.arange(N), side="right") - 1
+        group_of.append(g)
+        total += lv.lens[g]
+    for n in range(N):
+        for j in range(Hkv):
+            row = suffix_code(n, j) * (inp.suffix_lens[n] / total[n]) if total[n] else np.zeros(128)
+            for l, lv in enumerate(levels):
+                g = int(group_of[l][n])
+                if total[n]:
+                    row = row + level_code(l, g, j) * (lv.lens[g] / total[n])
+            if total[n]:
+                row[107:113] = _bits(j, 3)   # every token carries the head's bits: weights sum to 1
+            expect[n, j * G:(j + 1) * G] = row
+    with np.errstate(divide="ignore"):
+        lse = np.log(total)
+    return expect, np.repeat(lse[:, None], Hq, axis=1)

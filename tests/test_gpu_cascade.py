@@ -48,3 +48,36 @@ def test_cascade_equals_attention_over_concatenated_prefixes(dev, oracle, i):
     err = attention_errors(out, ref_out, inp.spec.dtype)
     lse_errors(lse, ref_lse, inp.spec.dtype)
     print(f"  max abs err {err:.3e}")
+
+
+def test_paper_shaped_tree_every_row(dev):
+    """The tree the paper's prompts form, at its own size (base prompt shared by all 26 tasks' 64
+    samples each, demonstrations by all of them, task text by a task's samples; 1664 samples), on
+    inputs whose result follows from the lengths alone (tests/owner_coded_inputs.py): zero keys,
+    value rows that carry 0/1 codes of level, group, sample and KV head.  Every row of the multi-level
+    call and of the same problem flattened to one level."""
+    from owner_coded_inputs import ownership_tree_problem
+    tasks, per_task = 26, 64
+    n = tasks * per_task
+    print(f"paper-shaped tree: {tasks} tasks x {per_task} samples, levels 4096 / 8192 / 512 tokens", flush=True)
+    inp = W.make_cascade_inputs([[n], [n], [per_task] * tasks], [(4096, 4096), (8192, 8192), (300, 512)],
+                                num_q_heads=32, num_kv_heads=8, suffix_len=(0, 1024), seed=5)
+    expect, expect_lse = ownership_tree_problem(inp)
+    zero = expect == 0
+    for name, d in (("levels", dev.DeviceCascade(inp)), ("flattened", dev.upload_attn(inp.flat))):
+        d.out.fill_(float("nan"))
+        d.lse.fill_(float("nan"))
+        d.run()
+        torch.cuda.synchronize()
+        got = d.out.float().cpu().numpy().astype(np.float64)
+        lse = d.lse.cpu().numpy().astype(np.float64)
+        del d
+        torch.cuda.empty_cache()
+        assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
+        assert np.all(got[zero] == 0), f"{name}: {int((got[zero] != 0).sum())} channels hold a foreign value row"
+        # half a unit in the last place of the bf16 result and of the fp16 partial states
+        rel = np.abs(got[~zero] - expect[~zero]) / expect[~zero]
+        assert rel.max() <= 2.0 ** -8 + 2.0 ** -10, (name, rel.max())
+        assert np.abs(lse - expect_lse).max() <= 2e-5, (name, np.abs(lse - expect_lse).max())
+        print(f"  {name}: rows {got.shape[0] * got.shape[1]}, max rel err {rel.max():.2e}, "
+              f"max lse err {np.abs(lse - expect_lse).max():.2e}", flush=True)

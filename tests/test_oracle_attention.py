@@ -303,3 +303,15 @@ def test_zero_keys_and_owner_coded_values_pin_the_bookkeeping(oracle, page_size)
     ref, ref_lse = oracle.attention_inputs(inp)
     assert np.abs(ref.reshape(expect.shape) - expect).max() <= 1e-14
     assert np.abs(ref_lse.reshape(expect_lse.shape) - expect_lse).max() <= 1e-14
+
+
+def test_owner_coded_tree_pins_the_flattened_form(oracle):
+    """The tree variant of the owner-coded inputs: the checker on the flattened problem must give the
+    means and token counts that follow from the levels' lengths."""
+    from owner_coded_inputs import ownership_tree_problem
+    inp = W.make_cascade_inputs(group_sizes=[[12], [5, 4, 3], [2, 3, 4, 3]], len_ranges=[(30, 30), (1, 40), (0, 9)],
+                                suffix_len=(0, 20), seed=77)
+    expect, expect_lse = ownership_tree_problem(inp)
+    ref, ref_lse = oracle.attention_inputs(inp.flat)
+    assert np.abs(ref.reshape(expect.shape) - expect).max() <= 1e-14
+    assert np.abs(ref_lse.reshape(expect_lse.shape) - expect_lse).max() <= 1e-14
