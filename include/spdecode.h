@@ -71,8 +71,10 @@ enum { SPD_STAGE_PREFIX = 1, SPD_STAGE_SUFFIX = 2, SPD_STAGE_MERGE = 4 };
  * sample_indptr[b] .. sample_indptr[b+1]-1.  Query head h reads KV head
  * h / (num_q_heads / num_kv_heads).
  *
- * Supported: dtype bf16 with head_dim 64 or 128 (MFMA path), dtype f32 with
- * head_dim <= 256 (plain path); page_size 0 (contiguous KV) or 16.
+ * Supported: dtype bf16 or f32, head_dim a multiple of 8 up to 256, page_size 0
+ * (contiguous KV) or 16.  bf16 with head_dim 128 and at most 16 query heads per
+ * KV head runs on the MFMA kernels; everything else on the plain kernels (fp32
+ * arithmetic, one lane per token).
  */
 typedef struct spd_attn_desc {
     int32_t dtype;                  /* spd_dtype of Q, K, V and the output */
