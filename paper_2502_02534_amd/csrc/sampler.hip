@@ -1306,8 +1306,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED
         }
         return kmax - prefix;
     };
-    // pairs written out by the covered slices: four per thread and slice, four slices at a time, all
-    // requested before any is used (unconditional loads from clamped positions; what lies past a slice's count is masked)
+    // pairs written out by the covered slices: four consecutive ones per thread and slice, four slices
+    // at a time, all requested before any is used (unconditional loads; what lies past a slice's count
+    // is masked).  A wavefront of the scan kernel lists its pairs segment by segment, so a thread's
+    // four pairs mostly belong to one 256-element segment: their kept mass is added up in the thread
+    // and goes to the segment's sum with one LDS addition per run of equal segments (one addition
+    // per pair would have most of a wavefront's lanes meet at one LDS address).
     static_assert(kEmitCap == 4 * kBlock, "four pairs per thread and slice");
     for (int s0 = 0; s0 < (FILTERED ? 0 : slices); s0 += 4) {
         unsigned long long ev[4][4];
@@ -1316,17 +1320,45 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(FILTERED
         for (int u = 0; u < 4; ++u) {
             const int s = min(s0 + u, slices - 1);
             cnt[u] = (s0 + u < slices && L.covered[s]) ? min(L.scount[s], kEmitCap) : 0;
-            const unsigned long long* e = W.emit + (size_t)s * kEmitCap;
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                ev[u][k] = e[tid + k * kBlock];
+            const ulonglong2* e = reinterpret_cast<const ulonglong2*>(W.emit + (size_t)s * kEmitCap) + 2 * tid;
+            const ulonglong2 a = e[0], b = e[1];
+            ev[u][0] = a.x;
+            ev[u][1] = a.y;
+            ev[u][2] = b.x;
+            ev[u][3] = b.y;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u) {
+            const int s = min(s0 + u, slices - 1);
+            const int mine = min(max(cnt[u] - 4 * tid, 0), 4);  // how many of the four places hold a pair
+            if (__builtin_amdgcn_ballot_w64(mine > 0) == 0ull)
+                continue;  // nothing in this wavefront's 256 places
+            double run = 0.0;   // kept mass of the present run of pairs of one segment
+            int run_seg = -1;
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                take(tid + k * kBlock < cnt[u], __uint_as_float((unsigned)ev[u][k]), (int)(ev[u][k] >> 32),
-                     min(s0 + u, slices - 1));
+            for (int k = 0; k < 4; ++k) {
+                const bool live = k < mine;
+                const float xq = __uint_as_float((unsigned)ev[u][k]);
+                const int idx = (int)(ev[u][k] >> 32);
+                const float t = xq * rc.c16;
+                const bool above = live && t >= t_above;
+                const bool candq = live && !above && t >= t_cand;
+                const float pq = live ? prob(xq, rs) : 0.f;
+                f_part += pq;
+                const int seg = s * kSegPerSlice + (int)((unsigned)(idx - s * slice_elems) / (unsigned)kSeg);
+                if (above && seg != run_seg && run_seg >= 0) {
+                    atomicAdd(&seg_mass[run_seg], run);
+                    run = 0.0;
+                }
+                if (above) {
+                    run_seg = seg;
+                    run += (double)pq;
+                }
+                append_masked(__builtin_amdgcn_ballot_w64(candq), candq, ev[u][k]);
+            }
+            if (run_seg >= 0)
+                atomicAdd(&seg_mass[run_seg], run);
+        }
         s_part += (double)f_part;
         f_part = 0.f;
     }
