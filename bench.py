@@ -80,8 +80,10 @@ def main() -> int:
     ap.add_argument("--loop-steps", type=int, default=24,
                     help="decode steps of the append + attention + sampler loop timed eagerly and as a "
                          "replayed graph (0 = skip; single-layer workloads only)")
+    ap.add_argument("--completion-steps", type=int, default=1024,
+                    help="tokens per sample of the end-to-end sampling job (64 samples, 8192-token prompt); 0 = skip")
     ap.add_argument("--no-also", action="store_true",
-                    help="skip the other configurations measured beside the main one (profiling runs)")
+                    help="skip the other configurations and the end-to-end job measured beside the main one (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an elementwise kernel over 256 MiB three times (reference for HBM traffic counters)")
     ap.add_argument("--page-order", choices=["shuffled", "sequential"], default="shuffled",
@@ -365,6 +367,60 @@ def main() -> int:
             del c2
             torch.cuda.empty_cache()
 
+    # ---- the paper's sampling job end to end: 64 samples of one 8192-token prompt, every sample from
+    # an empty suffix to `completion_steps` generated tokens, one captured decode step replayed ----------
+    completions = None
+    if args.completion_steps > 0 and not args.no_also:
+        torch.cuda.empty_cache()
+        sp3 = dataclasses.replace(workloads.SPECS[3], suffix_len=(0, args.completion_steps))
+        h3 = workloads.make_attn_inputs(3, spec=sp3)
+        h3.suffix_lens[:] = 0
+        sin3 = workloads.make_sampler_inputs(3)
+        rng = np.random.default_rng(4321)
+        rows = 16   # distinct per-step inputs; later steps reuse the last row (the timing does not depend on the values)
+
+        def draw3(shape):
+            t = torch.from_numpy(workloads.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))).cuda()
+            return t.view(torch.int16).view(torch.bfloat16)
+
+        n3 = sp3.num_samples
+        lp3 = device.DecodeLoop(device.upload_attn(h3), device.upload_sampler(sin3),
+                                draw3((rows, n3, sp3.num_q_heads, sp3.head_dim)),
+                                draw3((rows, n3, sp3.num_kv_heads, sp3.head_dim)),
+                                draw3((rows, n3, sp3.num_kv_heads, sp3.head_dim)),
+                                torch.from_numpy(rng.random((rows, n3), dtype=np.float32)).cuda(), -1)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            lp3.one_step()                      # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph3 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph3):
+            lp3.one_step()
+        graph3.replay()
+        torch.cuda.synchronize()
+        lp3.step.zero_()
+        lp3.attn.suffix_lens.zero_()
+        lp3.finished.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.completion_steps):
+            graph3.replay()
+        torch.cuda.synchronize()
+        total = time.perf_counter() - t0
+        final_lens = lp3.attn.suffix_lens.cpu().numpy()
+        assert int(final_lens.min()) == args.completion_steps == int(final_lens.max()), "the loop did not append every step"
+        completions = {"workload": "64 samples of one 8192-token prompt, suffixes grown from 0 to "
+                                   f"{args.completion_steps} tokens", "steps": args.completion_steps,
+                       "samples": n3, "total_ms": total * 1e3, "us_per_step_mean": total / args.completion_steps * 1e6,
+                       "tokens_per_sec": n3 * args.completion_steps / total,
+                       "note": "per step: decode_step_select + append_suffix_kv + attention + sample_tokens + "
+                               "decode_step_record, replayed from one captured graph; no host synchronisation "
+                               "between steps"}
+        del lp3, graph3
+        torch.cuda.empty_cache()
+
     line = {
         "metric": "decode_steps_per_sec", "value": 1e3 / ms_per_step, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -373,7 +429,8 @@ def main() -> int:
         "tokens_per_sec": sp.num_samples * 1e3 / ms_per_step,
         "step_algorithmic_bytes": step_bytes,
         "step_GBps": step_bytes / ms_per_step / 1e6,
-        "roofline": roofline, "kernels": kernels, "decode_loop": loop_info, "also": also, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "decode_loop": loop_info, "completions": completions, "also": also,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     return 0
