@@ -297,9 +297,9 @@ def main() -> int:
         graph_us = (time.perf_counter() - t0) / (L - 2) * 1e6
         loop_info = {"steps": L, "us_per_step_eager": eager_us, "us_per_step_graph": graph_us,
                      "tokens_per_sec_graph": sp.num_samples * 1e6 / graph_us,
-                     "note": "decode_step_select + append_suffix_kv + attention + sample_tokens + decode_step_record "
-                             "per step: library launches only, step counter and lengths on the device; "
-                             "graph = one captured step replayed"}
+                     "note": "decode_step_advance (record, select and KV append in one launch) + attention + "
+                             "sample_tokens per step: library launches only, step counter and lengths on the "
+                             "device; graph = one captured step replayed"}
         del lp, gl, graph, q_s, k_s, v_s, u_s
 
     if args.calibrate_copy:
@@ -415,9 +415,9 @@ def main() -> int:
                                    f"{args.completion_steps} tokens", "steps": args.completion_steps,
                        "samples": n3, "total_ms": total * 1e3, "us_per_step_mean": total / args.completion_steps * 1e6,
                        "tokens_per_sec": n3 * args.completion_steps / total,
-                       "note": "per step: decode_step_select + append_suffix_kv + attention + sample_tokens + "
-                               "decode_step_record, replayed from one captured graph; no host synchronisation "
-                               "between steps"}
+                       "note": "per step: decode_step_advance (record, select and KV append in one launch) + "
+                               "attention + sample_tokens, replayed from one captured graph; no host "
+                               "synchronisation between steps"}
         del lp3, graph3
         torch.cuda.empty_cache()
 

@@ -330,6 +330,44 @@ SPD_API int decode_step_select(int64_t *step_state, int64_t num_steps,
 SPD_API int decode_step_record(int64_t *step_state, int64_t num_steps,
                        int32_t count, const spd_row_copy *copies, void *stream);
 
+/*
+ * Everything between two decode steps of such a loop in ONE launch (a launch between two dependent
+ * kernels costs 4 to 5 us on this machine whatever it does, and select + append + record are three
+ * of the seven launches of a step).  With t = current:
+ *
+ *   - results of the step before, if t >= 1 (and t - 1 < num_steps): every `record` src (row_bytes
+ *     bytes) goes to row t - 1 of its dst ([num_steps, row_bytes]), and every sample's suffix
+ *     length, as that step left it, to row t - 1 of lens_record (int32 [num_steps, N], or NULL);
+ *   - inputs of this step: row t of every `select` src ([num_steps, row_bytes]) goes to its dst
+ *     (rows past the last one repeat the last one);
+ *   - append_suffix_kv with row t of k_steps / v_steps ([num_steps, N, Hkv, D], desc->dtype) as the
+ *     new token (same rules: finished samples and full slots are left alone);
+ *   - then current = next = t + 1, stored by whichever workgroup finishes last, after all have read
+ *     the old value (the third word of step_state counts them and is left at 0).  No workgroup
+ *     waits for another.
+ *
+ * step_state is int64 [3], {0, 0, 0} before the first step.  A loop is: advance, the step's calls,
+ * advance, the step's calls, ...; the results of the last step are still unrecorded when the loop
+ * ends, and one decode_step_record call (which writes row next - 1) records them.
+ * record_count and select_count may each be 0 .. SPD_MAX_STEP_COPIES; `record` and `select` are host
+ * memory read during the call; alignment rules as for decode_step_select, K/V pointers 16-byte
+ * aligned; the other arguments as for append_suffix_kv.  A kernel launch only (no memset, no
+ * allocation), fit for graph capture.  Calls on one step_state must not overlap.  Returns spd_status.
+ */
+SPD_API int decode_step_advance(int64_t *step_state, int64_t num_steps,
+                        int32_t record_count, const spd_row_copy *record,
+                        int32_t select_count, const spd_row_copy *select,
+                        const spd_attn_desc *desc,
+                        const void *k_steps, const void *v_steps,
+                        void *k_suffix, void *v_suffix,
+                        int32_t *suffix_lens,
+                        const int32_t *suffix_page_indptr,
+                        const int32_t *suffix_page_indices,
+                        int64_t max_suffix_len,
+                        const int32_t *last_tokens, int32_t end_token, int32_t *finished,
+                        int32_t *lens_record,
+                        void *stream);
+
 /* Short description of a status code (static storage). */
 SPD_API const char *spd_status_string(int status);
 

@@ -85,6 +85,10 @@ def load() -> ctypes.CDLL:
     for fn in (lib.decode_step_select, lib.decode_step_record):
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, i64, ctypes.c_int32, ctypes.POINTER(RowCopy), vp]
+    lib.decode_step_advance.restype = ctypes.c_int
+    lib.decode_step_advance.argtypes = ([vp, i64, ctypes.c_int32, ctypes.POINTER(RowCopy), ctypes.c_int32,
+                                         ctypes.POINTER(RowCopy), dp] + [vp] * 7 +
+                                        [i64, vp, ctypes.c_int32, vp, vp, vp])
     _lib = lib
     return lib
 
@@ -189,6 +193,19 @@ def decode_step_record(step_state, num_steps: int, copies, stream=None) -> None:
     rc = load().decode_step_record(_ptr(step_state), int(num_steps), len(copies), copies, _stream(stream))
     if rc != SPD_OK:
         raise SpdError(rc, "decode_step_record")
+
+
+def decode_step_advance(step_state, num_steps: int, record, select, desc: AttnDesc, k_steps, v_steps, k_suffix,
+                        v_suffix, suffix_lens, suffix_page_indptr, suffix_page_indices, max_suffix_len: int,
+                        last_tokens=None, end_token: int = -1, finished=None, lens_record=None, stream=None) -> None:
+    """`record` / `select`: ctypes arrays from make_row_copies, or None for no copies of that kind."""
+    rc = load().decode_step_advance(
+        _ptr(step_state), int(num_steps), 0 if record is None else len(record), record,
+        0 if select is None else len(select), select, ctypes.byref(desc), _ptr(k_steps), _ptr(v_steps),
+        _ptr(k_suffix), _ptr(v_suffix), _ptr(suffix_lens), _ptr(suffix_page_indptr), _ptr(suffix_page_indices),
+        int(max_suffix_len), _ptr(last_tokens), int(end_token), _ptr(finished), _ptr(lens_record), _stream(stream))
+    if rc != SPD_OK:
+        raise SpdError(rc, "decode_step_advance")
 
 
 def make_levels(levels):

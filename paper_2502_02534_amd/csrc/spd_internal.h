@@ -100,6 +100,24 @@ struct KvAppendParams {
     int* finished;            // may be null
 };
 
+// Everything between two decode steps in one launch: up to 2 * kMaxStepCopies row copies (each
+// either a record of the previous step's results or a selection of this step's inputs) and the
+// append, whose k_new / v_new point at [num_steps, N, Hkv, D] arrays.
+constexpr int kMaxAdvanceCopies = 2 * kMaxStepCopies;
+struct StepAdvanceParams {
+    long long* state;      // {current step, next step, arrivals}
+    long long num_steps;
+    int count;
+    int first_block[kMaxAdvanceCopies + 1];  // the last entry is the number of copy workgroups
+    const void* src[kMaxAdvanceCopies];
+    void* dst[kMaxAdvanceCopies];
+    long long row_bytes[kMaxAdvanceCopies];
+    int wide[kMaxAdvanceCopies];
+    int record[kMaxAdvanceCopies];           // 1: into row current - 1 of dst; 0: out of row current of src
+    KvAppendParams kv;
+    int* lens_record;      // [num_steps, N] or null
+};
+
 struct SamplerParams {
     const float* logits;
     long long rows, vocab, stride;
@@ -157,6 +175,7 @@ hipError_t launch_attn_merge(const AttnParams& p, hipStream_t s);
 hipError_t launch_kv_append(const KvAppendParams& a, hipStream_t s);
 long long step_rows_blocks(long long row_bytes);
 hipError_t launch_step_rows(const StepRowsParams& a, bool record, hipStream_t s);
+hipError_t launch_step_advance(const StepAdvanceParams& a, hipStream_t s);
 size_t sampler_workspace_bytes(long long rows, long long vocab);
 hipError_t launch_sampler(const SamplerParams& p, void* workspace, hipStream_t s);
 

@@ -130,6 +130,84 @@ int decode_step_record(int64_t* step_state, int64_t num_steps, int32_t count, co
     return step_rows(step_state, num_steps, count, copies, true, stream);
 }
 
+int decode_step_advance(int64_t* step_state, int64_t num_steps, int32_t record_count, const spd_row_copy* record,
+                        int32_t select_count, const spd_row_copy* select, const spd_attn_desc* desc,
+                        const void* k_steps, const void* v_steps, void* k_suffix, void* v_suffix, int32_t* suffix_lens,
+                        const int32_t* suffix_page_indptr, const int32_t* suffix_page_indices, int64_t max_suffix_len,
+                        const int32_t* last_tokens, int32_t end_token, int32_t* finished, int32_t* lens_record,
+                        void* stream)
+{
+    static_assert(2 * SPD_MAX_STEP_COPIES == spd::kMaxAdvanceCopies, "header and kernel agree on the number of copies");
+    if (!step_state || misaligned(step_state, 8) || num_steps < 1 || record_count < 0 ||
+        record_count > SPD_MAX_STEP_COPIES || select_count < 0 || select_count > SPD_MAX_STEP_COPIES ||
+        (record_count > 0 && !record) || (select_count > 0 && !select))
+        return SPD_EINVAL;
+    if (!desc)
+        return SPD_EINVAL;
+    const int rc = check_desc(desc);
+    if (rc != SPD_OK)
+        return rc;
+    if (!k_steps || !v_steps || !k_suffix || !v_suffix || !suffix_lens)
+        return SPD_EINVAL;
+    if (desc->page_size != 0 && (!suffix_page_indptr || !suffix_page_indices))
+        return SPD_EINVAL;
+    if (max_suffix_len < 0 || max_suffix_len > (1ll << 30))
+        return SPD_EINVAL;
+    const int elt = desc->dtype == SPD_BF16 ? 2 : 4;
+    if ((desc->head_dim * elt) % 16 != 0)
+        return SPD_EUNSUPPORTED;
+    if (misaligned(k_steps, 16) || misaligned(v_steps, 16) || misaligned(k_suffix, 16) || misaligned(v_suffix, 16))
+        return SPD_EINVAL;
+    spd::StepAdvanceParams a;
+    a.state = (long long*)step_state;
+    a.num_steps = num_steps;
+    a.count = record_count + select_count;
+    long long blocks = 0;
+    for (int i = 0; i < spd::kMaxAdvanceCopies; ++i) {
+        a.first_block[i] = (int)blocks;
+        a.src[i] = nullptr;
+        a.dst[i] = nullptr;
+        a.row_bytes[i] = 0;
+        a.wide[i] = 0;
+        a.record[i] = 0;
+        if (i >= a.count)
+            continue;
+        const bool is_record = i < record_count;
+        const spd_row_copy& c = is_record ? record[i] : select[i - record_count];
+        if (!c.src || !c.dst || c.row_bytes <= 0 || c.row_bytes % 4 != 0 || misaligned(c.src, 4) || misaligned(c.dst, 4))
+            return SPD_EINVAL;
+        a.src[i] = c.src;
+        a.dst[i] = c.dst;
+        a.row_bytes[i] = c.row_bytes;
+        a.wide[i] = (c.row_bytes % 16 == 0 && !misaligned(c.src, 16) && !misaligned(c.dst, 16)) ? 1 : 0;
+        a.record[i] = is_record ? 1 : 0;
+        blocks += spd::step_rows_blocks(c.row_bytes);
+        if (blocks > 0x3fffffffLL)
+            return SPD_EUNSUPPORTED;
+    }
+    a.first_block[spd::kMaxAdvanceCopies] = (int)blocks;
+    a.kv.N = desc->num_samples;
+    a.kv.Hkv = desc->num_kv_heads;
+    a.kv.D = desc->head_dim;
+    a.kv.elt = elt;
+    a.kv.page_size = desc->page_size;
+    a.kv.capacity = (int)max_suffix_len;
+    a.kv.k_new = k_steps;
+    a.kv.v_new = v_steps;
+    a.kv.k_suffix = k_suffix;
+    a.kv.v_suffix = v_suffix;
+    a.kv.suffix_lens = suffix_lens;
+    a.kv.page_indptr = suffix_page_indptr;
+    a.kv.pages = suffix_page_indices;
+    a.kv.last_tokens = last_tokens;
+    a.kv.end_token = end_token;
+    a.kv.finished = finished;
+    a.lens_record = lens_record;
+    if (blocks + a.kv.N > 0x7fffffffLL)
+        return SPD_EUNSUPPORTED;
+    return spd::launch_step_advance(a, (hipStream_t)stream) == hipSuccess ? SPD_OK : SPD_ELAUNCH;
+}
+
 const char* spd_status_string(int status)
 {
     switch (status) {

@@ -120,13 +120,14 @@ class DecodeLoop:
     and `lens_steps` record every step's results for checking."""
 
     def __init__(self, attn: DeviceAttn, sampler: DeviceSampler, q_steps, k_steps, v_steps, u_steps,
-                 end_token: int = -1):
+                 end_token: int = -1, one_launch: bool = True):
         self.attn, self.sampler = attn, sampler
+        self.one_launch = one_launch
         self.q_steps, self.k_steps, self.v_steps, self.u_steps = q_steps, k_steps, v_steps, u_steps
         self.steps = q_steps.shape[0]
         dev = q_steps.device
         n = attn.q.shape[0]
-        self.step = torch.zeros(2, dtype=torch.int64, device=dev)  # {current, next}
+        self.step = torch.zeros(3, dtype=torch.int64, device=dev)  # {current, next, arrivals}
         self.finished = torch.zeros(n, dtype=torch.int32, device=dev)
         self.end_token = end_token
         sampler.tokens.fill_(-1)  # "no token yet": never equal to an end token (>= 0)
@@ -142,10 +143,26 @@ class DecodeLoop:
         self._record = B.make_row_copies([(sampler.tokens, self.tokens_steps, nbytes(sampler.tokens)),
                                           (attn.out, self.out_steps, nbytes(attn.out)),
                                           (attn.suffix_lens, self.lens_steps, nbytes(attn.suffix_lens))])
+        # one launch per step: the lengths are recorded by the append itself, K and V rows are read
+        # straight from the step tensors
+        self._select_qu = B.make_row_copies([(q_steps, attn.q, nbytes(attn.q)),
+                                             (u_steps, sampler.uniforms, nbytes(sampler.uniforms))])
+        self._record_to = B.make_row_copies([(sampler.tokens, self.tokens_steps, nbytes(sampler.tokens)),
+                                             (attn.out, self.out_steps, nbytes(attn.out))])
 
     def one_step(self) -> None:
-        """Enqueues one decode step on the current stream (capturable: kernel launches only)."""
+        """Enqueues one decode step on the current stream (capturable: kernel launches only).  With
+        `one_launch` the results of a step are recorded by the next step's advance call, those of
+        the last step by `flush`."""
         a, s = self.attn, self.sampler
+        if self.one_launch:
+            B.decode_step_advance(self.step, self.steps, self._record_to, self._select_qu, a.desc, self.k_steps,
+                                  self.v_steps, a.k_suffix, a.v_suffix, a.suffix_lens, a.suffix_page_indptr,
+                                  a.suffix_page_indices, a.max_suffix_len, s.tokens, self.end_token, self.finished,
+                                  self.lens_steps)
+            a.run()
+            s.run()
+            return
         B.decode_step_select(self.step, self.steps, self._select)
         B.append_suffix_kv(a.desc, self.k_cur, self.v_cur, a.k_suffix, a.v_suffix, a.suffix_lens,
                            a.suffix_page_indptr, a.suffix_page_indices, a.max_suffix_len,
@@ -153,6 +170,11 @@ class DecodeLoop:
         a.run()
         s.run()
         B.decode_step_record(self.step, self.steps, self._record)
+
+    def flush(self) -> None:
+        """After the last step of a `one_launch` loop: records that step's results."""
+        if self.one_launch:
+            B.decode_step_record(self.step, self.steps, self._record)
 
 
 @dataclasses.dataclass

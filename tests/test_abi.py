@@ -157,3 +157,22 @@ def test_step_calls_check_their_arguments(lib):
         for bad in (B.RowCopy(0, 512, 64), B.RowCopy(256, 0, 64), B.RowCopy(256, 512, 0),
                     B.RowCopy(256, 512, 6), B.RowCopy(258, 512, 64), B.RowCopy(256, 514, 64)):
             assert fn(st, 4, 1, (B.RowCopy * 1)(bad), z) == 1
+    # the one-launch form: the same checks on both lists, then those of append_suffix_kv
+    desc = B.make_desc(dtype=B.SPD_BF16, num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=1, num_samples=4)
+    p = ctypes.c_void_p(4096)
+
+    def adv(state=st, steps=4, nrec=1, rec=ok, nsel=1, sel=ok, d=desc, k=p, v=p, ks=p, vs=p, lens=p, cap=64):
+        return lib.decode_step_advance(state, steps, nrec, rec, nsel, sel, ctypes.byref(d) if d is not None else None,
+                                       k, v, ks, vs, lens, z, z, cap, z, -1, z, z, z)
+
+    assert adv(state=z) == 1 and adv(state=ctypes.c_void_p(260)) == 1 and adv(steps=0) == 1
+    assert adv(nrec=9) == 1 and adv(nsel=9) == 1 and adv(nrec=-1) == 1
+    assert adv(nrec=1, rec=None) == 1 and adv(nsel=1, sel=None) == 1
+    assert adv(rec=(B.RowCopy * 1)(B.RowCopy(256, 512, 6))) == 1 and adv(sel=(B.RowCopy * 1)(B.RowCopy(0, 512, 64))) == 1
+    assert adv(d=None) == 1 and adv(k=z) == 1 and adv(v=z) == 1 and adv(ks=z) == 1 and adv(vs=z) == 1 and adv(lens=z) == 1
+    assert adv(k=ctypes.c_void_p(4100)) == 1 and adv(cap=-1) == 1
+    paged = B.make_desc(dtype=B.SPD_BF16, num_q_heads=8, num_kv_heads=2, head_dim=128, num_prompts=1, num_samples=4,
+                        page_size=16)
+    assert adv(d=paged) == 1                                     # paged KV without a page table
+    bad_dim = B.make_desc(dtype=B.SPD_BF16, num_q_heads=8, num_kv_heads=2, head_dim=264, num_prompts=1, num_samples=4)
+    assert adv(d=bad_dim) == 2

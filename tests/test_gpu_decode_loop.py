@@ -69,9 +69,13 @@ def _host_append(inp, n, pos, krow, vrow):
         inp.v_suffix[pg, :, pos % P, :] = vrow
 
 
+@pytest.mark.parametrize("one_launch", [False, True], ids=["three_launches", "one_launch"])
 @pytest.mark.parametrize("i", range(len(CASES)))
-def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i):
-    print(f"decode loop case {i}: {CASES[i]}", flush=True)
+def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i, one_launch):
+    """`one_launch`: select, append and record as one decode_step_advance call per step (the results
+    of a step are recorded by the next step's call, those of the last by a final record call);
+    otherwise as three calls."""
+    print(f"decode loop case {i}: {CASES[i]}, one_launch={one_launch}", flush=True)
     inp = W.make_attn_inputs(0, spec=W.small_spec(**CASES[i]), seed=700 + i)
     # leave every sample room for the steps inside its own slot / page list where it had any
     inp.suffix_lens = np.maximum(inp.suffix_lens - STEPS + 2, 0).astype(np.int32)
@@ -108,12 +112,14 @@ def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i):
         s = dev.upload_sampler(W.SamplerInputs(logits, temp, top_p, u[0].copy()))
         to = lambda x: torch.from_numpy(x).cuda()
         as_el = (lambda x: to(x).view(torch.int16).view(torch.bfloat16)) if bf16 else to
-        return dev.DecodeLoop(a, s, as_el(q), as_el(k), as_el(v), to(u), end_token)
+        return dev.DecodeLoop(a, s, as_el(q), as_el(k), as_el(v), to(u), end_token, one_launch=one_launch)
 
     loop = fresh_loop()
     for t in range(STEPS):
         loop.one_step()
+    loop.flush()
     torch.cuda.synchronize()
+    assert loop.step.tolist() == [STEPS, STEPS, 0]
     lens = loop.lens_steps.cpu().numpy()
     toks = loop.tokens_steps.cpu().numpy()
     outs = loop.out_steps.float().cpu().numpy().astype(np.float64)
@@ -146,6 +152,7 @@ def test_decode_loop_matches_checker_and_graph_replay(dev, oracle, i):
     for t in range(STEPS):
         graph.replay()
         _ = (g_loop.attn.out.float().sum() + t).item()   # eager kernel + host synchronisation between replays
+    g_loop.flush()
     torch.cuda.synchronize()
     assert torch.equal(g_loop.lens_steps, loop.lens_steps)
     assert torch.equal(g_loop.tokens_steps, loop.tokens_steps)
@@ -178,3 +185,54 @@ def test_step_select_and_record_follow_the_device_counter(dev):
         torch.cuda.synchronize()
         assert state.tolist() == [t + 1, t + 1]
     assert torch.equal(rec_big, big) and torch.equal(rec_odd, odd)
+
+
+def test_step_advance_records_selects_and_appends_in_one_launch(dev):
+    """decode_step_advance alone, against plain tensor arithmetic: the counter triple after every
+    call, rows selected (the last one repeated past the end), results recorded one call later
+    (nothing past the end), the new K/V rows in the suffix slots, lengths recorded before the
+    append, full slots and finished samples left alone."""
+    from paper_2502_02534_amd import binding as B
+    steps, n, hkv, d, cap = 4, 3, 2, 64, 5
+    g = torch.Generator(device="cpu").manual_seed(11)
+    rnd = lambda *shape: torch.randn(*shape, generator=g).cuda()
+    k_steps, v_steps = rnd(steps, n, hkv, d), rnd(steps, n, hkv, d)
+    x_steps = torch.randint(-2**31, 2**31 - 1, (steps, 50), dtype=torch.int32, generator=g).cuda()   # 200 B rows
+    x_now = torch.zeros(50, dtype=torch.int32).cuda()
+    result = torch.zeros(7, dtype=torch.int32).cuda()                                               # 28 B rows
+    result_steps = torch.full((steps, 7), -1, dtype=torch.int32).cuda()
+    k_suffix, v_suffix = torch.zeros(n, cap, hkv, d).cuda(), torch.zeros(n, cap, hkv, d).cuda()
+    lens0 = [0, 3, 5]                                             # sample 2 starts with a full slot
+    lens = torch.tensor(lens0, dtype=torch.int32).cuda()
+    lens_steps = torch.full((steps, n), -1, dtype=torch.int32).cuda()
+    tokens = torch.tensor([7, 7, 7], dtype=torch.int32).cuda()    # nobody's last token is the end token (9) yet
+    finished = torch.zeros(n, dtype=torch.int32).cuda()
+    desc = B.make_desc(dtype=B.SPD_F32, num_q_heads=hkv, num_kv_heads=hkv, head_dim=d, num_prompts=1, num_samples=n)
+    state = torch.zeros(3, dtype=torch.int64).cuda()
+    rec = B.make_row_copies([(result, result_steps, 28)])
+    sel = B.make_row_copies([(x_steps, x_now, 200)])
+    want_len = list(lens0)
+    want_k = torch.zeros_like(k_suffix)
+    done = [False] * n
+    for t in range(steps + 2):
+        if t == 2:
+            tokens[0] = 9                                          # sample 0 draws the end token in step 1
+        B.decode_step_advance(state, steps, rec, sel, desc, k_steps, v_steps, k_suffix, v_suffix, lens, None, None, cap,
+                              tokens, 9, finished, lens_steps)
+        torch.cuda.synchronize()
+        row = min(t, steps - 1)
+        assert state.tolist() == [t + 1, t + 1, 0]
+        assert torch.equal(x_now, x_steps[row])
+        if 1 <= t <= steps:
+            assert lens_steps[t - 1].tolist() == want_len          # the lengths the step before left
+            assert torch.equal(result_steps[t - 1], torch.full((7,), 100 + t - 1, dtype=torch.int32).cuda())
+        for s in range(n):
+            done[s] = done[s] or int(tokens[s]) == 9
+            if not done[s] and want_len[s] < cap:
+                want_k[s, want_len[s]] = k_steps[row, s]
+                want_len[s] += 1
+        assert lens.tolist() == want_len and finished.tolist() == [int(x) for x in done]
+        assert torch.equal(k_suffix, want_k)
+        result.fill_(100 + t)                                      # "the step's result"
+    assert (result_steps >= 100).all() and (lens_steps >= 0).all()
+    assert want_len == [2, 5, 5]
