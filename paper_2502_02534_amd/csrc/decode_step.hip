@@ -74,8 +74,8 @@ __global__ __launch_bounds__(kCopyThreads) void step_advance_kernel(StepAdvanceP
             copy_block((const char*)a.src[i], (char*)a.dst[i] + (t - 1) * nbytes, nbytes, blk, a.wide[i] != 0);
     } else {
         const int n = (int)blockIdx.x - copy_blocks;
-        const long long step_elems = (long long)a.kv.N * a.kv.Hkv * a.kv.D * a.kv.elt;  // bytes of one step's rows
-        append_sample(a.kv, n, (const char*)a.kv.k_new + row_in * step_elems, (const char*)a.kv.v_new + row_in * step_elems,
+        const long long step_bytes = (long long)a.kv.N * a.kv.Hkv * a.kv.D * a.kv.elt;  // one step of k_steps / v_steps
+        append_sample(a.kv, n, (const char*)a.kv.k_new + row_in * step_bytes, (const char*)a.kv.v_new + row_in * step_bytes,
                       a.lens_record && have_prev ? a.lens_record + (t - 1) * a.kv.N + n : nullptr);
     }
     __syncthreads();  // every thread of the workgroup has read what it needs of the state
